@@ -1,0 +1,143 @@
+/*
+ * libstreamindex -- lightning-indexer score + exact per-query top-k on one MI355X (gfx950).
+ *
+ * The operation (StreamIndex, Sections 1, 3, 4 and 5):
+ *
+ *   I(t, s)  = sum_h w[t,h] * ReLU( sum_d q[t,h,d] * K[s,d] )            (Section 1, Section 3)
+ *   legal(t) = T                          for SI_MASK_NONE
+ *            = min(T, floor((t+1)/m))     for SI_MASK_CAUSAL_BLOCK        (Section 4.2, Section 5)
+ *   out(t)   = the min(k, legal(t)) keys s < legal(t) that are largest under
+ *              (a,i) > (b,j)  <=>  a > b or (a == b and i < j)            (Section 4.1)
+ *              listed best first; the remaining slots hold idx = -1, score = -inf.
+ *
+ * It is computed as the chunked partition-merge stream of Algorithm 2: queries in tiles of
+ * c_S, keys in tiles of c_T, a running top-k buffer per query.  The [B,S,H,T] tensor is never
+ * formed; the largest transient is one [B, c_S, c_T] fp32 score tile inside `workspace`.
+ * The result does not depend on (c_S, c_T): it is bit-identical for every tiling.
+ *
+ * Conventions for every entry point
+ *   - q, K, w, out_idx, out_score, workspace and every other array argument marked "device"
+ *     are caller-owned DEVICE pointers (HBM), contiguous row-major, 16-byte aligned.
+ *     The library allocates no device memory and frees none.
+ *   - q and K hold bfloat16; w, scores hold IEEE float32.  Inputs must be finite.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *     enqueued on it; the call returns without synchronising.  Results are valid once the
+ *     caller has synchronised the stream.  `workspace` contents are undefined afterwards.
+ *   - Argument errors are detected on the host before anything is launched and reported as
+ *     a negative si_status; no exception crosses the boundary.
+ *   - Calls that share a workspace must not overlap in time.
+ */
+#ifndef STREAMINDEX_H
+#define STREAMINDEX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SI_OK = 0,
+    SI_ERR_INVALID_ARG = -1,        /* null pointer, non-positive size, bad enum               */
+    SI_ERR_UNSUPPORTED_SHAPE = -2,  /* D not in {32,64,128}, H_I > 64, k > 4096, T >= 2^31     */
+    SI_ERR_WORKSPACE_TOO_SMALL = -3,
+    SI_ERR_HIP = -4                 /* a HIP runtime call failed; see si_last_hip_error()      */
+} si_status;
+
+typedef enum {
+    SI_MASK_NONE = 0,          /* every key is legal for every query                          */
+    SI_MASK_CAUSAL_BLOCK = 1   /* key s legal for query t iff (s+1)*m <= t+1  (Section 4.2)    */
+} si_mask_mode;
+
+/* Problem size.  T is explicit (the causal mode does not require T == S/m). */
+typedef struct {
+    int32_t B;    /* batch                                  */
+    int32_t S;    /* queries per batch                      */
+    int32_t H_I;  /* indexer heads, 1..64                   */
+    int32_t D;    /* head dimension: 32, 64 or 128          */
+    int32_t T;    /* compressed keys per batch              */
+} si_dims;
+
+typedef struct {
+    int32_t c_S;             /* query tile                                                    */
+    int32_t c_T;             /* key tile                                                      */
+    size_t workspace_bytes;  /* what si_workspace_bytes returns for (c_S, c_T)                */
+} si_plan;
+
+/* Chunk-size rule of Section 6.5 restated for this chip: pick (c_S, c_T) whose workspace
+ * fits `hbm_budget_bytes`.  c_T is taken so that one key tile stays resident in an XCD's L2
+ * and c_S as large as the budget allows up to the point where the launch fills the chip a
+ * few times over.  Host only, no GPU call.  Fails with SI_ERR_WORKSPACE_TOO_SMALL when not
+ * even the smallest tiling fits. */
+si_status si_plan_tiles(const si_dims* dims, int32_t m, int32_t k, si_mask_mode mask_mode,
+                        size_t hbm_budget_bytes, si_plan* out);
+
+/* Bytes of workspace needed for a tiling: one fp32 score tile [B,c_S,c_T], the running
+ * buffer [B,c_S,k] of 64-bit (score,index) keys, a candidate buffer of the same size, and
+ * two int32 counters per row.  0 on invalid arguments. */
+size_t si_workspace_bytes(const si_dims* dims, int32_t k, int32_t c_S, int32_t c_T);
+
+/* The whole step (Algorithm 2) with the tiling chosen by si_plan_tiles for
+ * budget = workspace_bytes.
+ *   q         device [B,S,H_I,D] bf16        K  device [B,T,D] bf16      w  device [B,S,H_I] f32
+ *   out_idx   device [B,S,k] int32           out_score  device [B,S,k] f32
+ *   workspace device, workspace_bytes bytes, 256-byte aligned */
+si_status si_indexer_topk(const void* q, const void* K, const float* w, const si_dims* dims,
+                          int32_t m, int32_t k, si_mask_mode mask_mode, int32_t* out_idx,
+                          float* out_score, void* workspace, size_t workspace_bytes,
+                          void* stream);
+
+/* Same with an explicit tiling (the design-space sweeps of Section 6.5).  Any c_S >= 1,
+ * c_T >= 1 is accepted; values above S / T are clamped. */
+si_status si_indexer_topk_tiled(const void* q, const void* K, const float* w,
+                                const si_dims* dims, int32_t m, int32_t k,
+                                si_mask_mode mask_mode, int32_t c_S, int32_t c_T,
+                                int32_t* out_idx, float* out_score, void* workspace,
+                                size_t workspace_bytes, void* stream);
+
+/* Step "score tile" alone (the fused score kernel of Section 5): fp32 scores of queries
+ * [s0, s0+c_S) against keys [t0, t0+c_T) of every batch, ReLU and the weighted head sum
+ * done in registers.  tile: device [B, c_S, c_T] f32, row stride c_T.  Entries whose query
+ * or key lies outside the problem are not written.  With SI_MASK_CAUSAL_BLOCK, entries of
+ * keys that are illegal for their query may be left unwritten (they are never selected). */
+si_status si_score_tile(const void* q, const void* K, const float* w, const si_dims* dims,
+                        int32_t m, si_mask_mode mask_mode, int32_t s0, int32_t t0,
+                        int32_t c_S, int32_t c_T, float* tile, void* stream);
+
+/* Steps "per-tile select", "merge" and "write-out" alone, on scores the caller supplies
+ * (Algorithm 2 without the score kernel; Section 4.3 corollary):
+ *   scores  device [R, n_cols] f32;  legal  device [R] int32 or NULL (= n_cols for all rows)
+ * Row r's result is the top-min(k, legal[r]) of scores[r, 0:legal[r]] under the total order,
+ * reached by streaming column tiles of c_T through the running buffer.
+ *   out_idx device [R,k] int32, out_score device [R,k] f32.
+ * workspace needs si_workspace_bytes({B=1,S=R,..}, k, R, 1) bytes. */
+si_status si_topk_from_scores(const float* scores, int32_t R, int32_t n_cols,
+                              const int32_t* legal, int32_t k, int32_t c_T, int32_t* out_idx,
+                              float* out_score, void* workspace, size_t workspace_bytes,
+                              void* stream);
+
+/* B*S*H_I*T*4: bytes of the fp32 intermediate of the materialize path (Section 3), for
+ * reporting only. */
+uint64_t si_materialize_bytes(const si_dims* dims);
+
+/* Per-kernel timing for benchmarks.  When enabled, every kernel launch made by the entry
+ * points above is bracketed by HIP events on its stream.  si_profile_read synchronises
+ * those events and returns, per kernel class, the summed duration in milliseconds and the
+ * number of launches since the last reset.  Classes: 0 score tile, 1 select, 2 merge,
+ * 3 write-out, 4 buffer init.  Not thread safe; meant for a single benchmarking thread. */
+#define SI_PROFILE_CLASSES 5
+si_status si_profile_enable(int32_t on);
+si_status si_profile_reset(void);
+si_status si_profile_read(double* ms_per_class, int64_t* launches_per_class);
+
+const char* si_strerror(si_status status);
+/* hipError_t of the last failed HIP call made by this library on this thread (0 = none). */
+int32_t si_last_hip_error(void);
+/* Library version, major*10000 + minor*100 + patch. */
+int32_t si_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STREAMINDEX_H */

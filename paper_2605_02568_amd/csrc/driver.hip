@@ -1,0 +1,328 @@
+// Host driver: argument checks, tile planning, workspace carve-up and the nested tile loop
+// of Algorithm 2 (outer loop over query tiles, inner loop over key tiles, running top-k
+// buffer per query, write-out after the last key tile).  Key tiles that hold no legal key for
+// any query of the query tile are not visited (Algorithm 2 visits them; their masked entries
+// can never be selected, so the result is the same).
+
+#include <algorithm>
+#include <vector>
+
+#include "si_internal.h"
+
+namespace si {
+
+namespace {
+
+thread_local int32_t g_last_hip_error = 0;
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+si_status hip_fail(hipError_t e) {
+    g_last_hip_error = static_cast<int32_t>(e);
+    return SI_ERR_HIP;
+}
+
+// ---- per-kernel timing (benchmark aid) --------------------------------------------------
+struct Profiler {
+    bool on = false;
+    std::vector<hipEvent_t> pool;  // reused events
+    size_t used = 0;
+    struct Span { int cls; size_t begin, end; };
+    std::vector<Span> spans;
+    double ms[SI_PROFILE_CLASSES] = {0};
+    int64_t launches[SI_PROFILE_CLASSES] = {0};
+
+    hipError_t next_event(size_t* idx) {
+        if (used == pool.size()) {
+            hipEvent_t ev;
+            hipError_t e = hipEventCreate(&ev);
+            if (e != hipSuccess) return e;
+            pool.push_back(ev);
+        }
+        *idx = used++;
+        return hipSuccess;
+    }
+    // folds finished spans into the totals and frees the events for reuse
+    hipError_t drain() {
+        for (const Span& s : spans) {
+            hipError_t e = hipEventSynchronize(pool[s.end]);
+            if (e != hipSuccess) return e;
+            float t = 0.f;
+            e = hipEventElapsedTime(&t, pool[s.begin], pool[s.end]);
+            if (e != hipSuccess) return e;
+            ms[s.cls] += t;
+            launches[s.cls] += 1;
+        }
+        spans.clear();
+        used = 0;
+        return hipSuccess;
+    }
+};
+Profiler g_prof;
+
+// Brackets one launch with events when profiling is on.
+template <typename F>
+hipError_t timed(int cls, hipStream_t stream, F&& launch) {
+    if (!g_prof.on) return launch();
+    if (g_prof.spans.size() >= 8192) {  // bound the number of live events
+        hipError_t e = g_prof.drain();
+        if (e != hipSuccess) return e;
+    }
+    size_t b = 0, en = 0;
+    hipError_t e = g_prof.next_event(&b);
+    if (e != hipSuccess) return e;
+    e = g_prof.next_event(&en);
+    if (e != hipSuccess) return e;
+    e = hipEventRecord(g_prof.pool[b], stream);
+    if (e != hipSuccess) return e;
+    e = launch();
+    if (e != hipSuccess) return e;
+    e = hipEventRecord(g_prof.pool[en], stream);
+    if (e != hipSuccess) return e;
+    g_prof.spans.push_back({cls, b, en});
+    return hipSuccess;
+}
+
+si_status check_dims(const si_dims* d, int32_t m, int32_t k, int mask_mode) {
+    if (!d) return SI_ERR_INVALID_ARG;
+    if (d->B < 1 || d->S < 1 || d->H_I < 1 || d->D < 1 || d->T < 1) return SI_ERR_INVALID_ARG;
+    if (m < 1 || k < 1) return SI_ERR_INVALID_ARG;
+    if (mask_mode != SI_MASK_NONE && mask_mode != SI_MASK_CAUSAL_BLOCK) return SI_ERR_INVALID_ARG;
+    if (d->D != 32 && d->D != 64 && d->D != 128) return SI_ERR_UNSUPPORTED_SHAPE;
+    if (d->H_I > kMaxHeads || k > kMaxK) return SI_ERR_UNSUPPORTED_SHAPE;
+    return SI_OK;
+}
+
+size_t workspace_bytes_for(int64_t B, int64_t c_S, int64_t c_T, int64_t k) {
+    return carve_workspace(nullptr, B, c_S, c_T, k).bytes;
+}
+
+}  // namespace
+
+Workspace carve_workspace(void* base, int64_t B, int64_t c_S, int64_t c_T, int64_t k) {
+    Workspace ws;
+    const size_t rows = static_cast<size_t>(B) * static_cast<size_t>(c_S);
+    size_t off = 0;
+    char* p = static_cast<char*>(base);
+    ws.tile = reinterpret_cast<float*>(p + off);
+    off = align_up(off + rows * static_cast<size_t>(c_T) * sizeof(float), 256);
+    ws.run_keys = reinterpret_cast<key64_t*>(p + off);
+    off = align_up(off + rows * static_cast<size_t>(k) * sizeof(key64_t), 256);
+    ws.cand_keys = reinterpret_cast<key64_t*>(p + off);
+    off = align_up(off + rows * static_cast<size_t>(k) * sizeof(key64_t), 256);
+    ws.run_count = reinterpret_cast<int32_t*>(p + off);
+    off = align_up(off + rows * sizeof(int32_t), 256);
+    ws.cand_count = reinterpret_cast<int32_t*>(p + off);
+    off = align_up(off + rows * sizeof(int32_t), 256);
+    ws.bytes = off;
+    return ws;
+}
+
+}  // namespace si
+
+using namespace si;
+
+extern "C" {
+
+size_t si_workspace_bytes(const si_dims* dims, int32_t k, int32_t c_S, int32_t c_T) {
+    if (!dims || dims->B < 1 || dims->S < 1 || dims->T < 1 || k < 1 || c_S < 1 || c_T < 1) return 0;
+    const int64_t cs = std::min<int64_t>(c_S, dims->S);
+    const int64_t ct = std::min<int64_t>(c_T, dims->T);
+    return workspace_bytes_for(dims->B, cs, ct, k);
+}
+
+si_status si_plan_tiles(const si_dims* dims, int32_t m, int32_t k, si_mask_mode mask_mode,
+                        size_t hbm_budget_bytes, si_plan* out) {
+    si_status st = check_dims(dims, m, k, mask_mode);
+    if (st != SI_OK) return st;
+    if (!out) return SI_ERR_INVALID_ARG;
+    // Key tile: the K rows of one tile (c_T * D bf16) should stay resident in one XCD's 4 MiB
+    // L2 while every workgroup of the launch streams them: aim for 2 MiB.
+    int64_t c_T = std::min<int64_t>(dims->T, (2ll << 20) / (2ll * dims->D));
+    // Query tile: as large as the budget allows, up to 8192 rows per batch entry (1024
+    // workgroups of 8 queries: four rounds over 256 CUs), in multiples of the workgroup's 8.
+    const int64_t cap = std::min<int64_t>(dims->S, std::max<int64_t>(kQueriesPerBlock, 8192 / dims->B));
+    for (;;) {
+        int64_t c_S = cap;
+        while (c_S > kQueriesPerBlock && workspace_bytes_for(dims->B, c_S, c_T, k) > hbm_budget_bytes)
+            c_S = std::max<int64_t>(kQueriesPerBlock, (c_S / 2 + 7) / 8 * 8);
+        c_S = std::min<int64_t>(c_S, dims->S);
+        if (workspace_bytes_for(dims->B, c_S, c_T, k) <= hbm_budget_bytes) {
+            out->c_S = static_cast<int32_t>(c_S);
+            out->c_T = static_cast<int32_t>(c_T);
+            out->workspace_bytes = workspace_bytes_for(dims->B, c_S, c_T, k);
+            return SI_OK;
+        }
+        if (c_T <= 32) return SI_ERR_WORKSPACE_TOO_SMALL;
+        c_T = std::max<int64_t>(32, c_T / 2);
+    }
+}
+
+si_status si_score_tile(const void* q, const void* K, const float* w, const si_dims* dims,
+                        int32_t m, si_mask_mode mask_mode, int32_t s0, int32_t t0,
+                        int32_t c_S, int32_t c_T, float* tile, void* stream) {
+    si_status st = check_dims(dims, m, 1, mask_mode);
+    if (st != SI_OK) return st;
+    if (!q || !K || !w || !tile) return SI_ERR_INVALID_ARG;
+    if (s0 < 0 || t0 < 0 || c_S < 1 || c_T < 1 || s0 >= dims->S || t0 >= dims->T) return SI_ERR_INVALID_ARG;
+    const int32_t rows = std::min<int64_t>(c_S, static_cast<int64_t>(dims->S) - s0);
+    const int32_t width = std::min<int64_t>(c_T, static_cast<int64_t>(dims->T) - t0);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    hipError_t e = timed(kProfScore, hs, [&] {
+        return launch_score_tile(q, K, w, *dims, m, mask_mode, s0, t0, rows, width, c_S, c_T, tile, hs);
+    });
+    return e == hipSuccess ? SI_OK : hip_fail(e);
+}
+
+si_status si_indexer_topk_tiled(const void* q, const void* K, const float* w,
+                                const si_dims* dims, int32_t m, int32_t k,
+                                si_mask_mode mask_mode, int32_t c_S, int32_t c_T,
+                                int32_t* out_idx, float* out_score, void* workspace,
+                                size_t workspace_bytes, void* stream) {
+    si_status st = check_dims(dims, m, k, mask_mode);
+    if (st != SI_OK) return st;
+    if (!q || !K || !w || !out_idx || !out_score || !workspace) return SI_ERR_INVALID_ARG;
+    if (c_S < 1 || c_T < 1) return SI_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return SI_ERR_INVALID_ARG;
+    const si_dims d = *dims;
+    c_S = std::min(c_S, d.S);
+    c_T = std::min(c_T, d.T);
+    const Workspace ws = carve_workspace(workspace, d.B, c_S, c_T, k);
+    if (ws.bytes > workspace_bytes) return SI_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+
+    for (int64_t s0 = 0; s0 < d.S; s0 += c_S) {
+        const int32_t rows = static_cast<int32_t>(std::min<int64_t>(c_S, d.S - s0));
+        hipError_t e = timed(kProfInit, hs, [&] {
+            return launch_init_rows(ws.run_count, d.B * c_S, hs);
+        });
+        if (e != hipSuccess) return hip_fail(e);
+        // keys visible to the last query of this tile (Section 4.2); later key tiles are skipped
+        int64_t t_hi = d.T;
+        if (mask_mode == SI_MASK_CAUSAL_BLOCK) t_hi = std::min<int64_t>(d.T, (s0 + rows) / m);
+        for (int64_t t0 = 0; t0 < t_hi; t0 += c_T) {
+            const int32_t width = static_cast<int32_t>(std::min<int64_t>(c_T, d.T - t0));
+            e = timed(kProfScore, hs, [&] {
+                return launch_score_tile(q, K, w, d, m, mask_mode, static_cast<int32_t>(s0),
+                                         static_cast<int32_t>(t0), rows, width, c_S, c_T, ws.tile, hs);
+            });
+            if (e != hipSuccess) return hip_fail(e);
+            TopkTileArgs a;
+            a.scores = ws.tile;
+            a.B = d.B; a.rows = rows; a.tile_rows = c_S; a.tile_cols = c_T;
+            a.s0 = static_cast<int32_t>(s0); a.t0 = static_cast<int32_t>(t0); a.width = width;
+            a.col0 = 0;
+            a.T = d.T; a.m = m; a.mask_mode = mask_mode; a.k = k;
+            a.legal_rows = nullptr;
+            a.run_keys = ws.run_keys; a.run_count = ws.run_count;
+            a.cand_keys = ws.cand_keys; a.cand_count = ws.cand_count;
+            e = timed(kProfSelect, hs, [&] { return launch_select(a, hs); });
+            if (e != hipSuccess) return hip_fail(e);
+            e = timed(kProfMerge, hs, [&] { return launch_merge(a, hs); });
+            if (e != hipSuccess) return hip_fail(e);
+        }
+        e = timed(kProfWriteout, hs, [&] {
+            return launch_writeout(ws.run_keys, ws.run_count, d.B, rows, c_S, k, d.S, s0, out_idx,
+                                   out_score, hs);
+        });
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return SI_OK;
+}
+
+si_status si_indexer_topk(const void* q, const void* K, const float* w, const si_dims* dims,
+                          int32_t m, int32_t k, si_mask_mode mask_mode, int32_t* out_idx,
+                          float* out_score, void* workspace, size_t workspace_bytes,
+                          void* stream) {
+    si_plan plan;
+    si_status st = si_plan_tiles(dims, m, k, mask_mode, workspace_bytes, &plan);
+    if (st != SI_OK) return st;
+    return si_indexer_topk_tiled(q, K, w, dims, m, k, mask_mode, plan.c_S, plan.c_T, out_idx,
+                                 out_score, workspace, workspace_bytes, stream);
+}
+
+si_status si_topk_from_scores(const float* scores, int32_t R, int32_t n_cols,
+                              const int32_t* legal, int32_t k, int32_t c_T, int32_t* out_idx,
+                              float* out_score, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+    if (!scores || !out_idx || !out_score || !workspace) return SI_ERR_INVALID_ARG;
+    if (R < 1 || n_cols < 1 || k < 1 || c_T < 1) return SI_ERR_INVALID_ARG;
+    if (k > kMaxK) return SI_ERR_UNSUPPORTED_SHAPE;
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return SI_ERR_INVALID_ARG;
+    c_T = std::min(c_T, n_cols);
+    // no score tile of our own here: the caller's matrix is read in place
+    const Workspace ws = carve_workspace(workspace, 1, R, 1, k);
+    if (ws.bytes > workspace_bytes) return SI_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    hipError_t e = timed(kProfInit, hs, [&] { return launch_init_rows(ws.run_count, R, hs); });
+    if (e != hipSuccess) return hip_fail(e);
+    for (int64_t t0 = 0; t0 < n_cols; t0 += c_T) {
+        TopkTileArgs a;
+        a.scores = scores;
+        a.B = 1; a.rows = R; a.tile_rows = R; a.tile_cols = n_cols;
+        a.s0 = 0; a.t0 = static_cast<int32_t>(t0);
+        a.width = static_cast<int32_t>(std::min<int64_t>(c_T, n_cols - t0));
+        a.col0 = static_cast<int32_t>(t0);
+        a.T = n_cols; a.m = 1; a.mask_mode = SI_MASK_NONE; a.k = k;
+        a.legal_rows = legal;
+        a.run_keys = ws.run_keys; a.run_count = ws.run_count;
+        a.cand_keys = ws.cand_keys; a.cand_count = ws.cand_count;
+        e = timed(kProfSelect, hs, [&] { return launch_select(a, hs); });
+        if (e != hipSuccess) return hip_fail(e);
+        e = timed(kProfMerge, hs, [&] { return launch_merge(a, hs); });
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    e = timed(kProfWriteout, hs, [&] {
+        return launch_writeout(ws.run_keys, ws.run_count, 1, R, R, k, R, 0, out_idx, out_score, hs);
+    });
+    return e == hipSuccess ? SI_OK : hip_fail(e);
+}
+
+uint64_t si_materialize_bytes(const si_dims* dims) {
+    if (!dims) return 0;
+    return static_cast<uint64_t>(dims->B) * static_cast<uint64_t>(dims->S) *
+           static_cast<uint64_t>(dims->H_I) * static_cast<uint64_t>(dims->T) * 4ull;
+}
+
+si_status si_profile_enable(int32_t on) {
+    g_prof.on = on != 0;
+    return SI_OK;
+}
+
+si_status si_profile_reset(void) {
+    hipError_t e = g_prof.drain();
+    if (e != hipSuccess) return hip_fail(e);
+    for (int i = 0; i < SI_PROFILE_CLASSES; ++i) {
+        g_prof.ms[i] = 0.0;
+        g_prof.launches[i] = 0;
+    }
+    return SI_OK;
+}
+
+si_status si_profile_read(double* ms_per_class, int64_t* launches_per_class) {
+    if (!ms_per_class || !launches_per_class) return SI_ERR_INVALID_ARG;
+    hipError_t e = g_prof.drain();
+    if (e != hipSuccess) return hip_fail(e);
+    for (int i = 0; i < SI_PROFILE_CLASSES; ++i) {
+        ms_per_class[i] = g_prof.ms[i];
+        launches_per_class[i] = g_prof.launches[i];
+    }
+    return SI_OK;
+}
+
+const char* si_strerror(si_status status) {
+    switch (status) {
+        case SI_OK: return "ok";
+        case SI_ERR_INVALID_ARG: return "invalid argument";
+        case SI_ERR_UNSUPPORTED_SHAPE: return "unsupported shape (D in {32,64,128}, H_I <= 64, k <= 4096)";
+        case SI_ERR_WORKSPACE_TOO_SMALL: return "workspace too small for this tiling";
+        case SI_ERR_HIP: return "HIP runtime error (see si_last_hip_error)";
+    }
+    return "unknown status";
+}
+
+int32_t si_last_hip_error(void) { return g_last_hip_error; }
+
+int32_t si_version(void) { return 100; }
+
+}  // extern "C"

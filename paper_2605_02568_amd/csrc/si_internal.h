@@ -1,0 +1,89 @@
+// Internal declarations shared by the translation units of libstreamindex.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "streamindex.h"
+
+namespace si {
+
+// A (score, index) pair packed so that unsigned 64-bit comparison is the total order of
+// Section 4.1: larger key = better entry.  High word: order-preserving image of the fp32
+// score (-0 folded onto +0 so that they tie); low word: ~index, so that the smaller index
+// wins among equal scores.  0 is below every real key and marks an empty slot.
+typedef unsigned long long key64_t;
+
+__host__ __device__ inline uint32_t score_to_ordered(uint32_t bits) {
+    return bits ^ ((bits >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+}
+__host__ __device__ inline uint32_t ordered_to_score(uint32_t ord) {
+    return ord ^ ((ord >> 31) ? 0x80000000u : 0xFFFFFFFFu);
+}
+#ifdef __HIPCC__
+__device__ inline key64_t make_key(float score, uint32_t idx) {
+    const uint32_t ord = score_to_ordered(__float_as_uint(score + 0.0f));
+    return (static_cast<key64_t>(ord) << 32) | static_cast<key64_t>(0xFFFFFFFFu - idx);
+}
+__device__ inline float key_score(key64_t key) {
+    return __uint_as_float(ordered_to_score(static_cast<uint32_t>(key >> 32)));
+}
+__device__ inline int32_t key_index(key64_t key) {
+    return static_cast<int32_t>(0xFFFFFFFFu - static_cast<uint32_t>(key));
+}
+// Section 4.2: number of legal keys of query position t.
+__device__ inline int32_t legal_count(int32_t t, int32_t T, int32_t m, int32_t mask_mode) {
+    if (mask_mode == SI_MASK_NONE) return T;
+    const int64_t blocks = (static_cast<int64_t>(t) + 1) / m;
+    return blocks < T ? static_cast<int32_t>(blocks) : T;
+}
+#endif
+
+constexpr int kMaxK = 4096;
+constexpr int kMaxHeads = 64;
+constexpr int kQueriesPerBlock = 8;  // score kernel: one query per wave, 8 waves
+
+// Carve-up of the caller's workspace.
+struct Workspace {
+    float* tile;          // [B, c_S, c_T]
+    key64_t* run_keys;    // [B*c_S, k] sorted best first, run_count valid
+    key64_t* cand_keys;   // [B*c_S, k] unsorted, cand_count valid
+    int32_t* run_count;   // [B*c_S]
+    int32_t* cand_count;  // [B*c_S]
+    size_t bytes;
+};
+Workspace carve_workspace(void* base, int64_t B, int64_t c_S, int64_t c_T, int64_t k);
+
+enum ProfileClass { kProfScore = 0, kProfSelect = 1, kProfMerge = 2, kProfWriteout = 3, kProfInit = 4 };
+
+// Kernel launchers (each enqueues exactly one kernel on `stream`).
+hipError_t launch_score_tile(const void* q, const void* K, const float* w, const si_dims& d,
+                             int32_t m, int32_t mask_mode, int32_t s0, int32_t t0, int32_t rows,
+                             int32_t width, int32_t tile_rows, int32_t tile_cols, float* tile,
+                             hipStream_t stream);
+
+// scores row r of batch b: scores + (b*tile_rows + r)*tile_cols.  Query position of row r is
+// s0 + r when legal_rows == nullptr (legal count from the mask), else legal_rows[b*tile_rows+r]
+// is the row's legal count over the whole key axis.
+struct TopkTileArgs {
+    const float* scores;
+    int32_t B, rows, tile_rows, tile_cols;  // rows <= tile_rows live rows per batch
+    int32_t s0, t0, width;                  // key tile [t0, t0+width)
+    int32_t col0;                           // column of `scores` that holds key t0
+    int32_t T, m, mask_mode, k;
+    const int32_t* legal_rows;
+    key64_t* run_keys;
+    int32_t* run_count;
+    key64_t* cand_keys;
+    int32_t* cand_count;
+};
+hipError_t launch_init_rows(int32_t* run_count, int32_t n, hipStream_t stream);
+hipError_t launch_select(const TopkTileArgs& a, hipStream_t stream);
+hipError_t launch_merge(const TopkTileArgs& a, hipStream_t stream);
+hipError_t launch_writeout(const key64_t* run_keys, const int32_t* run_count, int32_t B,
+                           int32_t rows, int32_t tile_rows, int32_t k, int64_t out_batch_stride,
+                           int64_t out_row0, int32_t* out_idx, float* out_score,
+                           hipStream_t stream);
+
+}  // namespace si

@@ -1,0 +1,105 @@
+"""CPU-only: the C-ABI library loads, exports what include/streamindex.h declares, and its
+host-side logic (planning, sizes, argument checks before any launch) behaves."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2605_02568_amd as P
+from paper_2605_02568_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GiB = 1 << 30
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "streamindex.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(si_[a-z_]+)\s*\(", hdr))
+    assert declared == set(binding.EXPORTS), declared ^ set(binding.EXPORTS)
+    lib = ctypes.CDLL(P.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert P.si_version() >= 100
+
+
+def test_strerror_and_sizes():
+    assert P.si_strerror(0) == "ok"
+    for code in (-1, -2, -3, -4):
+        assert P.si_strerror(code) not in ("ok", "unknown status")
+    # Section 1: 256 GB at S=65536 with H_I=64, T=S/4
+    assert P.si_materialize_bytes(1, 65536, 64, 128, 16384) == 256 * GiB
+    # workspace = score tile + running buffer + candidate buffer + counters
+    ws = P.si_workspace_bytes(1, 1 << 20, 64, 128, 1 << 18, 1024, 2048, 8192)
+    expect = 2048 * 8192 * 4 + 2 * 2048 * 1024 * 8 + 2 * 2048 * 4
+    assert expect <= ws <= expect + 5 * 256
+    assert P.si_workspace_bytes(1, 100, 4, 32, 25, 16, 4096, 4096) == \
+        P.si_workspace_bytes(1, 100, 4, 32, 25, 16, 100, 25)  # clamped to the problem
+    assert P.si_workspace_bytes(1, 100, 4, 32, 25, 0, 8, 8) == 0
+
+
+def test_plan_respects_budget_and_shapes():
+    # 1M context under 8 GB (headline configuration)
+    c_S, c_T, ws = P.si_plan_tiles(1, 1 << 20, 64, 128, 1 << 18, 4, 1024, 1, 8 * 10**9)
+    assert ws <= 8 * 10**9 and c_T * 128 * 2 <= 2 << 20 and c_S % 8 == 0 and c_S >= 2048
+    assert ws == P.si_workspace_bytes(1, 1 << 20, 64, 128, 1 << 18, 1024, c_S, c_T)
+    # a tight budget shrinks the query tile first, then the key tile
+    c_S2, c_T2, ws2 = P.si_plan_tiles(1, 1 << 20, 64, 128, 1 << 18, 4, 1024, 1, 8 << 20)
+    assert ws2 <= 8 << 20 and c_S2 < c_S and c_S2 >= 8
+    c_S3, c_T3, ws3 = P.si_plan_tiles(1, 1 << 20, 64, 128, 1 << 18, 4, 1024, 1, 200 << 10)
+    assert ws3 <= 200 << 10 and c_S3 == 8 and c_T3 < c_T2
+    with pytest.raises(P.StreamIndexError) as e:
+        P.si_plan_tiles(1, 1 << 20, 64, 128, 1 << 18, 4, 1024, 1, 1024)
+    assert e.value.status == P.SI_ERR_WORKSPACE_TOO_SMALL
+    # small problems are clamped to their own size
+    c_S, c_T, _ = P.si_plan_tiles(1, 1024, 4, 32, 256, 4, 16, 0, 1 << 30)
+    assert (c_S, c_T) == (1024, 256)
+
+
+@pytest.mark.parametrize("bad,status", [
+    (dict(D=48), P.SI_ERR_UNSUPPORTED_SHAPE),
+    (dict(H_I=65), P.SI_ERR_UNSUPPORTED_SHAPE),
+    (dict(k=4097), P.SI_ERR_UNSUPPORTED_SHAPE),
+    (dict(k=0), P.SI_ERR_INVALID_ARG),
+    (dict(m=0), P.SI_ERR_INVALID_ARG),
+    (dict(S=0), P.SI_ERR_INVALID_ARG),
+    (dict(mask=2), P.SI_ERR_INVALID_ARG),
+])
+def test_argument_errors_are_reported_before_any_launch(bad, status):
+    a = dict(B=1, S=64, H_I=4, D=32, T=16, m=4, k=8, mask=1)
+    a.update(bad)
+    lib = P.load()
+    dims = binding.si_dims(a["B"], a["S"], a["H_I"], a["D"], a["T"])
+    plan = binding.si_plan()
+    assert lib.si_plan_tiles(ctypes.byref(dims), a["m"], a["k"], a["mask"], 1 << 30,
+                             ctypes.byref(plan)) == status
+    # the compute entry point rejects the same arguments on the host (pointers are never used)
+    fake = ctypes.c_void_p(256)
+    rc = lib.si_indexer_topk(fake, fake, fake, ctypes.byref(dims), a["m"], a["k"], a["mask"],
+                             fake, fake, fake, 1 << 30, None)
+    assert rc == status
+
+
+def test_null_pointers_and_small_workspace_rejected():
+    lib = P.load()
+    dims = binding.si_dims(1, 64, 4, 32, 16)
+    fake = ctypes.c_void_p(256)
+    assert lib.si_indexer_topk(None, fake, fake, ctypes.byref(dims), 4, 8, 1, fake, fake, fake,
+                               1 << 30, None) == P.SI_ERR_INVALID_ARG
+    assert lib.si_indexer_topk_tiled(fake, fake, fake, ctypes.byref(dims), 4, 8, 1, 64, 16, fake,
+                                     fake, fake, 16, None) == P.SI_ERR_WORKSPACE_TOO_SMALL
+    assert lib.si_indexer_topk_tiled(fake, fake, fake, ctypes.byref(dims), 4, 8, 1, 64, 16, fake,
+                                     fake, ctypes.c_void_p(264), 1 << 30, None) == P.SI_ERR_INVALID_ARG
+    assert lib.si_topk_from_scores(None, 4, 4, None, 2, 2, fake, fake, fake, 1 << 20, None) \
+        == P.SI_ERR_INVALID_ARG
+    assert lib.si_profile_read(None, None) == P.SI_ERR_INVALID_ARG
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2605_02568_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower().replace("no cpu fallback", ""), (dirpath, f)

@@ -1,0 +1,251 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU oracle on the
+same seeded inputs.  Run with `-m gpu` on an MI355X."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_02568_amd as P
+import workloads as W
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _workspace(nbytes):
+    return torch.empty(int(nbytes), dtype=torch.uint8, device=DEV)
+
+
+def _run_tiled(q, K, w, wl_m, k, mask_mode, c_S, c_T):
+    B, S, H, D = q.shape
+    T = K.shape[1]
+    out_idx = torch.full((B, S, k), -7, dtype=torch.int32, device=DEV)
+    out_score = torch.full((B, S, k), 123.0, dtype=torch.float32, device=DEV)
+    ws = _workspace(P.si_workspace_bytes(B, S, H, D, T, k, c_S, c_T))
+    P.si_indexer_topk_tiled(q, K, w, wl_m, k, mask_mode, c_S, c_T, out_idx, out_score, ws)
+    torch.cuda.synchronize()
+    return out_idx, out_score
+
+
+def _rand_problem(seed, B, S, H, D, T):
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    q = torch.randn((B, S, H, D), generator=g).to(torch.bfloat16)
+    K = torch.randn((B, T, D), generator=g).to(torch.bfloat16)
+    w = torch.randn((B, S, H), generator=g) / np.sqrt(H)
+    return q, K, w
+
+
+# ------------------------------------------------------------------ step a1/a2: score tile
+@pytest.mark.parametrize("B,S,H,D,T,s0,t0,c_S,c_T", [
+    (1, 64, 4, 32, 48, 0, 0, 64, 48),       # tiny head shape, one tile
+    (2, 37, 33, 64, 200, 5, 32, 19, 131),   # ragged everything, two head blocks, batch 2
+    (1, 300, 64, 128, 700, 8, 128, 280, 512),  # V4 head shape, several key chunks + ragged tail
+    (1, 16, 17, 128, 40, 3, 7, 9, 33),      # tile origin not aligned to anything
+])
+def test_score_tile_matches_oracle(oracle, B, S, H, D, T, s0, t0, c_S, c_T):
+    _say(f"score_tile B={B} S={S} H={H} D={D} T={T} s0={s0} t0={t0} c_S={c_S} c_T={c_T}")
+    q, K, w = _rand_problem(1, B, S, H, D, T)
+    tile = torch.full((B, c_S, c_T), float("nan"), dtype=torch.float32, device=DEV)
+    P.si_score_tile(q.to(DEV), K.to(DEV), w.to(DEV), 1, P.SI_MASK_NONE, s0, t0, c_S, c_T, tile)
+    torch.cuda.synchronize()
+    got = tile.cpu().numpy()
+    qb, Kb, wn = W.bf16_bits(q), W.bf16_bits(K), w.numpy()
+    rows = min(c_S, S - s0)
+    width = min(c_T, T - t0)
+    for b in range(B):
+        for r in range(rows):
+            ref = oracle.score_row(qb[b, s0 + r], Kb[b], wn[b, s0 + r])[t0:t0 + width]
+            err = np.abs(got[b, r, :width] - ref)
+            assert np.all(err <= parity.tol(ref)), (b, r, err.max())
+            assert np.all(err <= 1e-4 * (np.abs(ref) + 1)), (b, r, err.max())  # fp32-level in practice
+    # nothing outside the live part of the tile is written
+    assert np.isnan(got[:, rows:, :]).all() and np.isnan(got[:, :, width:]).all()
+
+
+def test_score_tile_causal_covers_every_legal_entry(oracle):
+    B, S, H, D, m = 1, 96, 8, 32, 4
+    T = S // m
+    q, K, w = _rand_problem(2, B, S, H, D, T)
+    tile = torch.full((B, S, T), float("nan"), dtype=torch.float32, device=DEV)
+    P.si_score_tile(q.to(DEV), K.to(DEV), w.to(DEV), m, P.SI_MASK_CAUSAL_BLOCK, 0, 0, S, T, tile)
+    torch.cuda.synchronize()
+    got = tile.cpu().numpy()
+    qb, Kb, wn = W.bf16_bits(q), W.bf16_bits(K), w.numpy()
+    for t in range(S):
+        L = (t + 1) // m
+        ref = oracle.score_row(qb[0, t], Kb[0], wn[0, t], L)
+        assert np.all(np.abs(got[0, t, :L] - ref) <= parity.tol(ref))
+
+
+def test_score_does_not_depend_on_tile_position():
+    """The same (query, key) pair must get the same bits wherever it falls in a tile."""
+    B, S, H, D, T = 1, 40, 64, 128, 300
+    q, K, w = _rand_problem(3, B, S, H, D, T)
+    qd, Kd, wd = q.to(DEV), K.to(DEV), w.to(DEV)
+    full = torch.zeros((B, S, T), dtype=torch.float32, device=DEV)
+    P.si_score_tile(qd, Kd, wd, 1, P.SI_MASK_NONE, 0, 0, S, T, full)
+    for (s0, t0, c_S, c_T) in [(1, 1, 17, 100), (7, 33, 33, 267), (13, 129, 8, 31)]:
+        part = torch.zeros((B, c_S, c_T), dtype=torch.float32, device=DEV)
+        P.si_score_tile(qd, Kd, wd, 1, P.SI_MASK_NONE, s0, t0, c_S, c_T, part)
+        torch.cuda.synchronize()
+        rows, width = min(c_S, S - s0), min(c_T, T - t0)
+        a = full[0, s0:s0 + rows, t0:t0 + width].cpu().numpy().view(np.uint32)
+        b = part[0, :rows, :width].cpu().numpy().view(np.uint32)
+        assert np.array_equal(a, b), (s0, t0)
+
+
+# ------------------------------------------------------------------ steps a3-a5: select, merge, write-out
+def _score_cases():
+    rng = np.random.default_rng(5)
+    R, n = 24, 3000
+    cases = {}
+    cases["normal"] = rng.standard_normal((R, n)).astype(np.float32)
+    cases["ties"] = (rng.integers(-3, 4, size=(R, n)) * 0.5).astype(np.float32)
+    cases["ascending"] = np.tile(np.arange(n, dtype=np.float32), (R, 1))
+    cases["descending"] = np.tile(-np.arange(n, dtype=np.float32), (R, 1))
+    cases["all_equal"] = np.full((R, n), 2.5, dtype=np.float32)
+    z = np.zeros((R, n), dtype=np.float32)
+    z[:, ::2] = -0.0  # +0 and -0 tie: index order decides
+    z[:, 5::7] = 1e-30
+    cases["signed_zero"] = z
+    big = rng.standard_normal((R, n)).astype(np.float32)
+    big[:, ::3] *= 1e30
+    big[:, 1::5] *= 1e-30
+    cases["wide_range"] = big
+    return cases
+
+
+@pytest.mark.parametrize("name", ["normal", "ties", "ascending", "descending", "all_equal",
+                                  "signed_zero", "wide_range"])
+def test_topk_from_scores_is_bit_exact(oracle, name):
+    sc = _score_cases()[name]
+    R, n = sc.shape
+    rng = np.random.default_rng(6)
+    legal = rng.integers(0, n + 1, size=R).astype(np.int32)
+    legal[:4] = [0, 1, n, n - 1]
+    scd = torch.from_numpy(sc).to(DEV)
+    for k, c_T in [(1, 64), (16, 7), (100, 256), (512, 300), (512, 3000), (1024, 1024), (4096, 1000)]:
+        for lg in (None, legal):
+            _say(f"topk_from_scores {name} k={k} c_T={c_T} legal={'yes' if lg is not None else 'no'}")
+            out_idx = torch.full((R, k), -7, dtype=torch.int32, device=DEV)
+            out_score = torch.full((R, k), 9.0, dtype=torch.float32, device=DEV)
+            ws = _workspace(P.si_workspace_bytes(1, R, 1, 32, n, k, R, 1))
+            lgd = None if lg is None else torch.from_numpy(lg).to(DEV)
+            P.si_topk_from_scores(scd, lgd, k, c_T, out_idx, out_score, ws)
+            torch.cuda.synchronize()
+            gi, gs = out_idx.cpu().numpy(), out_score.cpu().numpy()
+            for r in range(R):
+                L = n if lg is None else int(lg[r])
+                ri, rs = oracle.sort_topk(sc[r, :L].astype(np.float64), k)
+                assert np.array_equal(gi[r], ri), (name, k, c_T, r, L)
+                ke = min(k, L)
+                # scores come back bit for bit, except that -0 may be returned as +0
+                assert np.array_equal(gs[r, :ke] + 0.0, rs[:ke].astype(np.float32) + 0.0)
+                assert np.all(np.isneginf(gs[r, ke:]))
+
+
+# ------------------------------------------------------------------ whole path
+def _check_all_rows(oracle, wl, q, K, w, out_idx, out_score):
+    B, S, H, D = q.shape
+    qb = W.bf16_bits(q).reshape(B * S, H, D)
+    Kb = W.bf16_bits(K)
+    wn = w.cpu().numpy().reshape(B * S, H)
+    b = np.repeat(np.arange(B, dtype=np.int32), S)
+    t = np.tile(np.arange(S, dtype=np.int64), B)
+    return parity.check_rows(oracle, qb, wn, Kb, b, t, wl.m, wl.k, wl.mask_mode,
+                             out_idx.cpu().numpy().reshape(B * S, wl.k),
+                             out_score.cpu().numpy().reshape(B * S, wl.k))
+
+
+def test_tiny_config_all_rows_and_planted_keys(oracle):
+    wl = W.CONFIGS["tiny"]
+    q, K, w, info = W.make_inputs(wl)
+    qd, Kd, wd = q.to(DEV), K.to(DEV), w.to(DEV)
+    ref = None
+    for c_S, c_T in [(1024, 256), (64, 32), (100, 7), (8, 256), (333, 100)]:
+        _say(f"tiny c_S={c_S} c_T={c_T}")
+        oi, os_ = _run_tiled(qd, Kd, wd, wl.m, wl.k, wl.mask_mode, c_S, c_T)
+        if ref is None:
+            stats = _check_all_rows(oracle, wl, q, K, w, oi, os_)
+            _say(f"tiny stats {stats}")
+            assert stats["min_recall"] == 1.0
+            t = info["t_star"]
+            assert set(oi[0, t, :wl.planted].cpu().tolist()) == set(info["planted_keys"])
+            ref = (oi, os_)
+        else:  # bit-identical across tilings
+            assert torch.equal(oi, ref[0]) and torch.equal(os_.view(torch.int32), ref[1].view(torch.int32))
+
+
+def test_flash_4k_all_rows(oracle):
+    wl = W.CONFIGS["flash_4k"]
+    q, K, w, _ = W.make_inputs(wl)
+    qd, Kd, wd = q.to(DEV), K.to(DEV), w.to(DEV)
+    ref = None
+    for c_S, c_T in [(4096, 1024), (512, 256), (1000, 333), (2048, 512)]:  # 256 < k: saturated tiles
+        _say(f"flash_4k c_S={c_S} c_T={c_T}")
+        oi, os_ = _run_tiled(qd, Kd, wd, wl.m, wl.k, wl.mask_mode, c_S, c_T)
+        if ref is None:
+            stats = _check_all_rows(oracle, wl, q, K, w, oi, os_)
+            _say(f"flash_4k stats {stats}")
+            assert stats["mean_recall"] > 0.9999
+            ref = (oi, os_)
+        else:
+            assert torch.equal(oi, ref[0]) and torch.equal(os_.view(torch.int32), ref[1].view(torch.int32))
+    # the planned entry point gives the same bits
+    out_idx = torch.empty_like(ref[0])
+    out_score = torch.empty_like(ref[1])
+    ws = _workspace(64 << 20)
+    P.si_indexer_topk(qd, Kd, wd, wl.m, wl.k, wl.mask_mode, out_idx, out_score, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out_idx, ref[0]) and torch.equal(out_score.view(torch.int32), ref[1].view(torch.int32))
+
+
+@pytest.mark.parametrize("B,S,H,D,m,k,mask", [
+    (2, 203, 4, 32, 4, 16, 1),     # batch 2, ragged S
+    (3, 64, 33, 64, 1, 70, 0),     # k > T: pads without a mask
+    (1, 129, 64, 128, 3, 5, 1),    # m does not divide S
+    (1, 50, 1, 32, 4, 4096, 1),    # largest k, single head
+])
+def test_odd_shapes_all_rows(oracle, B, S, H, D, m, k, mask):
+    T = max(1, S // m)
+    q, K, w = _rand_problem(7, B, S, H, D, T)
+    wl = W.Workload("odd", B, S, H, D, m, k, mask)
+    ref = None
+    for c_S, c_T in [(S, T), (13, 11), (8, 1)]:
+        _say(f"odd B={B} S={S} H={H} D={D} m={m} k={k} c_S={c_S} c_T={c_T}")
+        oi, os_ = _run_tiled(q.to(DEV), K.to(DEV), w.to(DEV), m, k, mask, c_S, c_T)
+        if ref is None:
+            B_, S_, H_, D_ = q.shape
+            stats = parity.check_rows(
+                oracle, W.bf16_bits(q).reshape(B * S, H, D), w.numpy().reshape(B * S, H),
+                W.bf16_bits(K), np.repeat(np.arange(B, dtype=np.int32), S),
+                np.tile(np.arange(S, dtype=np.int64), B), m, k, mask,
+                oi.cpu().numpy().reshape(B * S, k), os_.cpu().numpy().reshape(B * S, k))
+            assert stats["min_recall"] == 1.0, stats
+            ref = (oi, os_)
+        else:
+            assert torch.equal(oi, ref[0]) and torch.equal(os_.view(torch.int32), ref[1].view(torch.int32))
+
+
+def test_duplicate_keys_and_zero_weights_tie_break(oracle):
+    B, S, H, D, m, k = 1, 64, 8, 32, 1, 12
+    T = 64
+    q, K, w = _rand_problem(8, B, S, H, D, T)
+    K[0, 40] = K[0, 9]
+    K[0, 41] = K[0, 9]
+    w[0, 5] = 0.0  # row 5: every score is 0 -> keys 0..k-1
+    oi, os_ = _run_tiled(q.to(DEV), K.to(DEV), w.to(DEV), m, k, 0, 16, 16)
+    ri, rs = oracle.topk_all(W.bf16_bits(q), W.bf16_bits(K), w.numpy(), m, k, 0)
+    assert oi[0, 5].cpu().tolist() == list(range(k))
+    assert torch.all(os_[0, 5] == 0)
+    got = oi.cpu().numpy()
+    for t in range(S):
+        row = list(got[0, t])
+        present = [s for s in (9, 40, 41) if s in row]
+        assert present == sorted(present) and present == [9, 40, 41][:len(present)]
+    assert np.array_equal(got, ri)  # this small case has no near-ties besides the planted exact ones
