@@ -19,14 +19,16 @@ def host_threads() -> int:
 
 
 def check_rows(oracle, q_rows, w_rows, K_bits, b_of_row, t_of_row, m, k, mask_mode,
-               gpu_idx, gpu_score, n_threads=None):
+               gpu_idx, gpu_score, n_threads=None, oracle_out=None):
     """q_rows [n,H,D] uint16, w_rows [n,H] f32, K_bits [B,T,D] uint16, gpu_idx/gpu_score [n,k].
     Raises AssertionError on the first violated rule; returns a stats dict."""
     n_threads = n_threads or host_threads()
     n = q_rows.shape[0]
     T = K_bits.shape[1]
-    ora_idx, ora_score = oracle.topk_rows(q_rows, w_rows, K_bits, b_of_row, t_of_row, m, k,
-                                          mask_mode, n_threads=n_threads)
+    if oracle_out is None:
+        oracle_out = oracle.topk_rows(q_rows, w_rows, K_bits, b_of_row, t_of_row, m, k,
+                                      mask_mode, n_threads=n_threads)
+    ora_idx, ora_score = oracle_out
     recalls, swaps, max_err, exact_rows, checked_pairs = [], 0, 0.0, 0, 0
     for r in range(n):
         t = int(t_of_row[r])
