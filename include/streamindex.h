@@ -12,7 +12,8 @@
  *
  * It is computed as the chunked partition-merge stream of Algorithm 2: queries in tiles of
  * c_S, keys in tiles of c_T, a running top-k buffer per query.  The [B,S,H,T] tensor is never
- * formed; the largest transient is one [B, c_S, c_T] fp32 score tile inside `workspace`.
+ * formed; the largest transient is one candidate list of at most c_T (score, index) pairs per
+ * query of the current query tile, inside `workspace` (O(B * c_S * c_T) bytes).
  * The result does not depend on (c_S, c_T): it is bit-identical for every tiling.
  *
  * Conventions for every entry point
@@ -73,9 +74,9 @@ typedef struct {
 si_status si_plan_tiles(const si_dims* dims, int32_t m, int32_t k, si_mask_mode mask_mode,
                         size_t hbm_budget_bytes, si_plan* out);
 
-/* Bytes of workspace needed for a tiling: one fp32 score tile [B,c_S,c_T], the running
- * buffer [B,c_S,k] of 64-bit (score,index) keys, a candidate buffer of the same size, and
- * two int32 counters per row.  0 on invalid arguments. */
+/* Bytes of workspace needed for a tiling: the running buffer [B,c_S,k] and the candidate
+ * buffer [B,c_S,c_T] of 64-bit (score,index) keys, and two int32 counters per row (c_S, c_T
+ * clamped to S, T).  0 on invalid arguments. */
 size_t si_workspace_bytes(const si_dims* dims, int32_t k, int32_t c_S, int32_t c_T);
 
 /* The whole step (Algorithm 2) with the tiling chosen by si_plan_tiles for
@@ -111,7 +112,7 @@ si_status si_score_tile(const void* q, const void* K, const float* w, const si_d
  * Row r's result is the top-min(k, legal[r]) of scores[r, 0:legal[r]] under the total order,
  * reached by streaming column tiles of c_T through the running buffer.
  *   out_idx device [R,k] int32, out_score device [R,k] f32.
- * workspace needs si_workspace_bytes({B=1,S=R,..}, k, R, 1) bytes. */
+ * workspace needs si_workspace_bytes({B=1, S=R, T=max(n_cols,k), ..}, k, c_S=R, c_T=k) bytes. */
 si_status si_topk_from_scores(const float* scores, int32_t R, int32_t n_cols,
                               const int32_t* legal, int32_t k, int32_t c_T, int32_t* out_idx,
                               float* out_score, void* workspace, size_t workspace_bytes,
@@ -124,7 +125,7 @@ uint64_t si_materialize_bytes(const si_dims* dims);
 /* Per-kernel timing for benchmarks.  When enabled, every kernel launch made by the entry
  * points above is bracketed by HIP events on its stream.  si_profile_read synchronises
  * those events and returns, per kernel class, the summed duration in milliseconds and the
- * number of launches since the last reset.  Classes: 0 score tile, 1 select, 2 merge,
+ * number of launches since the last reset.  Classes: 0 score tile, 1 select, 2 select+merge,
  * 3 write-out, 4 buffer init.  Not thread safe; meant for a single benchmarking thread. */
 #define SI_PROFILE_CLASSES 5
 si_status si_profile_enable(int32_t on);

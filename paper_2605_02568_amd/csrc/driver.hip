@@ -93,23 +93,32 @@ si_status check_dims(const si_dims* d, int32_t m, int32_t k, int mask_mode) {
     return SI_OK;
 }
 
+// The fused path keeps, per query row of a tile, k running keys and up to c_T candidates.
 size_t workspace_bytes_for(int64_t B, int64_t c_S, int64_t c_T, int64_t k) {
-    return carve_workspace(nullptr, B, c_S, c_T, k).bytes;
+    return carve_workspace(nullptr, B * c_S, k, std::max<int64_t>(c_T, 1)).bytes;
+}
+
+// Key tiles of one query tile: a narrow first tile, then widths that double up to c_T.  The
+// first tile cannot be filtered (no k-th best exists yet), so it is kept small; each later
+// tile is filtered against the top-k of everything before it.  The result does not depend on
+// this schedule.
+int64_t next_width(int64_t t0, int64_t c_T, int64_t k) {
+    const int64_t first = std::max<int64_t>(2 * k, 1024);
+    const int64_t w = t0 == 0 ? first : std::max<int64_t>(t0, first);
+    return std::min<int64_t>(w, c_T);
 }
 
 }  // namespace
 
-Workspace carve_workspace(void* base, int64_t B, int64_t c_S, int64_t c_T, int64_t k) {
+Workspace carve_workspace(void* base, int64_t rows_, int64_t k, int64_t cand_stride) {
     Workspace ws;
-    const size_t rows = static_cast<size_t>(B) * static_cast<size_t>(c_S);
+    const size_t rows = static_cast<size_t>(rows_);
     size_t off = 0;
     char* p = static_cast<char*>(base);
-    ws.tile = reinterpret_cast<float*>(p + off);
-    off = align_up(off + rows * static_cast<size_t>(c_T) * sizeof(float), 256);
     ws.run_keys = reinterpret_cast<key64_t*>(p + off);
     off = align_up(off + rows * static_cast<size_t>(k) * sizeof(key64_t), 256);
     ws.cand_keys = reinterpret_cast<key64_t*>(p + off);
-    off = align_up(off + rows * static_cast<size_t>(k) * sizeof(key64_t), 256);
+    off = align_up(off + rows * static_cast<size_t>(cand_stride) * sizeof(key64_t), 256);
     ws.run_count = reinterpret_cast<int32_t*>(p + off);
     off = align_up(off + rows * sizeof(int32_t), 256);
     ws.cand_count = reinterpret_cast<int32_t*>(p + off);
@@ -187,7 +196,7 @@ si_status si_indexer_topk_tiled(const void* q, const void* K, const float* w,
     const si_dims d = *dims;
     c_S = std::min(c_S, d.S);
     c_T = std::min(c_T, d.T);
-    const Workspace ws = carve_workspace(workspace, d.B, c_S, c_T, k);
+    const Workspace ws = carve_workspace(workspace, static_cast<int64_t>(d.B) * c_S, k, c_T);
     if (ws.bytes > workspace_bytes) return SI_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t hs = static_cast<hipStream_t>(stream);
 
@@ -200,26 +209,22 @@ si_status si_indexer_topk_tiled(const void* q, const void* K, const float* w,
         // keys visible to the last query of this tile (Section 4.2); later key tiles are skipped
         int64_t t_hi = d.T;
         if (mask_mode == SI_MASK_CAUSAL_BLOCK) t_hi = std::min<int64_t>(d.T, (s0 + rows) / m);
-        for (int64_t t0 = 0; t0 < t_hi; t0 += c_T) {
-            const int32_t width = static_cast<int32_t>(std::min<int64_t>(c_T, d.T - t0));
+        for (int64_t t0 = 0; t0 < t_hi;) {
+            const int32_t width = static_cast<int32_t>(std::min<int64_t>(next_width(t0, c_T, k), d.T - t0));
             e = timed(kProfScore, hs, [&] {
-                return launch_score_tile(q, K, w, d, m, mask_mode, static_cast<int32_t>(s0),
-                                         static_cast<int32_t>(t0), rows, width, c_S, c_T, ws.tile, hs);
+                return launch_score_filter(q, K, w, d, m, mask_mode, static_cast<int32_t>(s0),
+                                           static_cast<int32_t>(t0), rows, width, c_S, ws.run_keys,
+                                           ws.run_count, ws.cand_keys, ws.cand_count, k, c_T, hs);
             });
             if (e != hipSuccess) return hip_fail(e);
-            TopkTileArgs a;
-            a.scores = ws.tile;
-            a.B = d.B; a.rows = rows; a.tile_rows = c_S; a.tile_cols = c_T;
-            a.s0 = static_cast<int32_t>(s0); a.t0 = static_cast<int32_t>(t0); a.width = width;
-            a.col0 = 0;
-            a.T = d.T; a.m = m; a.mask_mode = mask_mode; a.k = k;
-            a.legal_rows = nullptr;
+            TopkTileArgs a{};
+            a.B = d.B; a.rows = rows; a.tile_rows = c_S;
+            a.k = k; a.cand_stride = c_T;
             a.run_keys = ws.run_keys; a.run_count = ws.run_count;
             a.cand_keys = ws.cand_keys; a.cand_count = ws.cand_count;
-            e = timed(kProfSelect, hs, [&] { return launch_select(a, hs); });
-            if (e != hipSuccess) return hip_fail(e);
             e = timed(kProfMerge, hs, [&] { return launch_merge(a, hs); });
             if (e != hipSuccess) return hip_fail(e);
+            t0 += width;
         }
         e = timed(kProfWriteout, hs, [&] {
             return launch_writeout(ws.run_keys, ws.run_count, d.B, rows, c_S, k, d.S, s0, out_idx,
@@ -251,18 +256,19 @@ si_status si_topk_from_scores(const float* scores, int32_t R, int32_t n_cols,
     if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return SI_ERR_INVALID_ARG;
     c_T = std::min(c_T, n_cols);
     // no score tile of our own here: the caller's matrix is read in place
-    const Workspace ws = carve_workspace(workspace, 1, R, 1, k);
+    const Workspace ws = carve_workspace(workspace, R, k, k);
     if (ws.bytes > workspace_bytes) return SI_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t hs = static_cast<hipStream_t>(stream);
     hipError_t e = timed(kProfInit, hs, [&] { return launch_init_rows(ws.run_count, R, hs); });
     if (e != hipSuccess) return hip_fail(e);
     for (int64_t t0 = 0; t0 < n_cols; t0 += c_T) {
-        TopkTileArgs a;
+        TopkTileArgs a{};
         a.scores = scores;
         a.B = 1; a.rows = R; a.tile_rows = R; a.tile_cols = n_cols;
         a.s0 = 0; a.t0 = static_cast<int32_t>(t0);
         a.width = static_cast<int32_t>(std::min<int64_t>(c_T, n_cols - t0));
         a.col0 = static_cast<int32_t>(t0);
+        a.cand_stride = k;
         a.T = n_cols; a.m = 1; a.mask_mode = SI_MASK_NONE; a.k = k;
         a.legal_rows = legal;
         a.run_keys = ws.run_keys; a.run_count = ws.run_count;

@@ -46,14 +46,13 @@ constexpr int kQueriesPerBlock = 8;  // score kernel: one query per wave, 8 wave
 
 // Carve-up of the caller's workspace.
 struct Workspace {
-    float* tile;          // [B, c_S, c_T]
-    key64_t* run_keys;    // [B*c_S, k] sorted best first, run_count valid
-    key64_t* cand_keys;   // [B*c_S, k] unsorted, cand_count valid
-    int32_t* run_count;   // [B*c_S]
-    int32_t* cand_count;  // [B*c_S]
+    key64_t* run_keys;    // [rows, k] sorted best first, run_count valid
+    key64_t* cand_keys;   // [rows, cand_stride] unsorted, cand_count valid
+    int32_t* run_count;   // [rows]
+    int32_t* cand_count;  // [rows]
     size_t bytes;
 };
-Workspace carve_workspace(void* base, int64_t B, int64_t c_S, int64_t c_T, int64_t k);
+Workspace carve_workspace(void* base, int64_t rows, int64_t k, int64_t cand_stride);
 
 enum ProfileClass { kProfScore = 0, kProfSelect = 1, kProfMerge = 2, kProfWriteout = 3, kProfInit = 4 };
 
@@ -71,6 +70,7 @@ struct TopkTileArgs {
     int32_t B, rows, tile_rows, tile_cols;  // rows <= tile_rows live rows per batch
     int32_t s0, t0, width;                  // key tile [t0, t0+width)
     int32_t col0;                           // column of `scores` that holds key t0
+    int32_t cand_stride;                    // slots per row in cand_keys
     int32_t T, m, mask_mode, k;
     const int32_t* legal_rows;
     key64_t* run_keys;
@@ -78,6 +78,13 @@ struct TopkTileArgs {
     key64_t* cand_keys;
     int32_t* cand_count;
 };
+// Score tile fused with the mask and the first half of the select: appends, per row, the
+// legal entries that beat the row's current k-th best to cand_keys and sets cand_count.
+hipError_t launch_score_filter(const void* q, const void* K, const float* w, const si_dims& d,
+                               int32_t m, int32_t mask_mode, int32_t s0, int32_t t0, int32_t rows,
+                               int32_t width, int32_t tile_rows, const key64_t* run_keys,
+                               const int32_t* run_count, key64_t* cand_keys, int32_t* cand_count,
+                               int32_t k, int32_t cand_stride, hipStream_t stream);
 hipError_t launch_init_rows(int32_t* run_count, int32_t n, hipStream_t stream);
 hipError_t launch_select(const TopkTileArgs& a, hipStream_t stream);
 hipError_t launch_merge(const TopkTileArgs& a, hipStream_t stream);

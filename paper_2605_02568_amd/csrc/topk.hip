@@ -5,12 +5,13 @@
 // (see make_key), so a tie on score is always resolved towards the smaller key index and
 // the final top-k set is unique: whatever the tiling, the same keys come out.
 //
-// select : one workgroup per query row of the tile.  Candidates are the row's legal tile
-//          entries that beat the row's current k-th best (entries that do not can never
-//          enter the final top-k).  If at most k survive, all are kept (this is also the
-//          "saturated tile" branch of Section 6.6: a tile narrower than k keeps every
-//          entry); otherwise an MSB-first radix descent over the 64-bit keys finds the
-//          k-th largest and exactly k are kept.
+// select : exact top-min(k, n) of one row's candidates.  If at most k candidates exist all
+//          are kept (this is also the "saturated tile" branch of Section 6.6: a tile narrower
+//          than k keeps every entry); otherwise an MSB-first radix descent over the 64-bit
+//          keys (8 bits per pass, LDS histogram) finds the k-th largest and exactly k are kept.
+//          Two front ends share it: select_kernel reads a dense fp32 score tile (and first
+//          drops entries that do not beat the row's current k-th best); merge_kernel applies
+//          it to a candidate list that the fused score kernel has already filtered.
 // merge  : one workgroup per row.  Candidates are sorted in LDS (bitonic), then each element
 //          of the two sorted lists finds its rank in the union by binary search in the other
 //          list; ranks below k are written back as the new running buffer.
@@ -21,6 +22,12 @@
 namespace si {
 
 constexpr int kTopkThreads = 256;
+
+struct SelectShared {
+    int hist[256];
+    int tmp;
+    int digit, need, bin;
+};
 
 __device__ inline int block_sum(int v, int* s_scratch) {
     // wave reduce, then one LDS atomic per wave
@@ -35,11 +42,45 @@ __device__ inline int block_sum(int v, int* s_scratch) {
     return total;
 }
 
-__global__ __launch_bounds__(kTopkThreads) void select_kernel(TopkTileArgs a) {
-    __shared__ int s_hist[256];
-    __shared__ int s_tmp;
-    __shared__ int s_digit, s_need, s_bin;
+// Threshold key `thr` such that exactly k of the n keys produced by fetch(j), j in [0,n),
+// that are > floor satisfy key >= thr.  Requires more than k such keys.  All threads of the
+// workgroup call it with the same arguments.
+template <typename Fetch>
+__device__ inline key64_t radix_kth(Fetch fetch, int n, key64_t floor_key, int k, SelectShared& sh) {
+    const int tid = threadIdx.x;
+    key64_t prefix = 0ull;
+    int need = k;
+    for (int shift = 56; shift >= 0; shift -= 8) {
+        sh.hist[tid] = 0;
+        __syncthreads();
+        for (int j = tid; j < n; j += kTopkThreads) {
+            const key64_t key = fetch(j);
+            const bool in_prefix = (shift == 56) || ((key >> (shift + 8)) == (prefix >> (shift + 8)));
+            if (key > floor_key && in_prefix) atomicAdd(&sh.hist[(key >> shift) & 255ull], 1);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            int cum = 0, d = 255;
+            for (; d > 0; --d) {
+                if (cum + sh.hist[d] >= need) break;
+                cum += sh.hist[d];
+            }
+            sh.digit = d;
+            sh.need = need - cum;
+            sh.bin = sh.hist[d];
+        }
+        __syncthreads();
+        prefix |= static_cast<key64_t>(sh.digit) << shift;
+        need = sh.need;
+        const bool whole_bin = (sh.bin == need);
+        __syncthreads();
+        if (whole_bin) break;  // every key of this bin is kept: prefix is the threshold
+    }
+    return prefix;
+}
 
+__global__ __launch_bounds__(kTopkThreads) void select_kernel(TopkTileArgs a) {
+    __shared__ SelectShared sh;
     const int tid = threadIdx.x;
     const int64_t row = static_cast<int64_t>(blockIdx.y) * a.tile_rows + blockIdx.x;
     const int L = a.legal_rows ? a.legal_rows[row]
@@ -52,54 +93,24 @@ __global__ __launch_bounds__(kTopkThreads) void select_kernel(TopkTileArgs a) {
     const float* sc = a.scores + row * a.tile_cols + a.col0;
     const int k = a.k;
     const key64_t theta = (a.run_count[row] == k) ? a.run_keys[row * k + k - 1] : 0ull;
-    key64_t* cand = a.cand_keys + row * k;
+    key64_t* cand = a.cand_keys + row * a.cand_stride;
     const uint32_t idx0 = static_cast<uint32_t>(a.t0);
+    auto fetch = [&](int j) { return make_key(sc[j], idx0 + j); };
 
     // survivors: entries strictly better than the current k-th best
     int mine = 0;
-    for (int j = tid; j < n; j += kTopkThreads) mine += make_key(sc[j], idx0 + j) > theta;
-    const int c = block_sum(mine, &s_tmp);
+    for (int j = tid; j < n; j += kTopkThreads) mine += fetch(j) > theta;
+    const int c = block_sum(mine, &sh.tmp);
 
     key64_t thr = theta + 1ull;  // keep key >= thr
-    if (c > k) {
-        // radix descent, 8 bits at a time from the top, for the k-th largest survivor
-        key64_t prefix = 0ull;
-        int need = k;
-        for (int shift = 56; shift >= 0; shift -= 8) {
-            s_hist[tid] = 0;
-            __syncthreads();
-            for (int j = tid; j < n; j += kTopkThreads) {
-                const key64_t key = make_key(sc[j], idx0 + j);
-                const bool in_prefix = (shift == 56) || ((key >> (shift + 8)) == (prefix >> (shift + 8)));
-                if (key > theta && in_prefix) atomicAdd(&s_hist[(key >> shift) & 255ull], 1);
-            }
-            __syncthreads();
-            if (tid == 0) {
-                int cum = 0, d = 255;
-                for (; d > 0; --d) {
-                    if (cum + s_hist[d] >= need) break;
-                    cum += s_hist[d];
-                }
-                s_digit = d;
-                s_need = need - cum;
-                s_bin = s_hist[d];
-            }
-            __syncthreads();
-            prefix |= static_cast<key64_t>(s_digit) << shift;
-            need = s_need;
-            const bool whole_bin = (s_bin == need);
-            __syncthreads();
-            if (whole_bin) break;  // every key of this bin is kept: prefix is the threshold
-        }
-        thr = prefix;
-    }
+    if (c > k) thr = radix_kth(fetch, n, theta, k, sh);
 
-    if (tid == 0) s_tmp = 0;
+    if (tid == 0) sh.tmp = 0;
     __syncthreads();
     for (int j = tid; j < n; j += kTopkThreads) {
-        const key64_t key = make_key(sc[j], idx0 + j);
+        const key64_t key = fetch(j);
         if (key >= thr) {
-            const int pos = atomicAdd(&s_tmp, 1);
+            const int pos = atomicAdd(&sh.tmp, 1);
             if (pos < k) cand[pos] = key;  // pos < k always holds; the guard keeps a logic slip in bounds
         }
     }
@@ -108,24 +119,44 @@ __global__ __launch_bounds__(kTopkThreads) void select_kernel(TopkTileArgs a) {
 
 __global__ __launch_bounds__(kTopkThreads) void merge_kernel(TopkTileArgs a, int pow2_k) {
     extern __shared__ key64_t smem[];
+    __shared__ SelectShared sh;
     key64_t* s_cand = smem;           // [pow2_k]
     key64_t* s_run = smem + pow2_k;   // [k]
 
     const int tid = threadIdx.x;
     const int64_t row = static_cast<int64_t>(blockIdx.y) * a.tile_rows + blockIdx.x;
-    const int c = a.cand_count[row];
+    int c = a.cand_count[row];
     if (c == 0) return;
     const int k = a.k;
     const int rc = a.run_count[row];
     key64_t* run = a.run_keys + row * k;
-    const key64_t* cand = a.cand_keys + row * k;
+    const key64_t* cand = a.cand_keys + row * a.cand_stride;
 
-    int P = 1;
-    while (P < c) P <<= 1;
-    for (int i = tid; i < P; i += kTopkThreads) s_cand[i] = (i < c) ? cand[i] : 0ull;
+    if (c > k) {
+        // more candidates than slots: keep exactly the k best of them
+        auto fetch = [&](int j) { return cand[j]; };
+        const key64_t thr = radix_kth(fetch, c, 0ull, k, sh);
+        if (tid == 0) sh.tmp = 0;
+        __syncthreads();
+        for (int j = tid; j < c; j += kTopkThreads) {
+            const key64_t key = cand[j];
+            if (key >= thr) {
+                const int pos = atomicAdd(&sh.tmp, 1);
+                if (pos < k) s_cand[pos] = key;
+            }
+        }
+        c = k;
+        for (int i = k + tid; i < pow2_k; i += kTopkThreads) s_cand[i] = 0ull;
+    } else {
+        int P = 1;
+        while (P < c) P <<= 1;
+        for (int i = tid; i < P; i += kTopkThreads) s_cand[i] = (i < c) ? cand[i] : 0ull;
+    }
     for (int i = tid; i < rc; i += kTopkThreads) s_run[i] = run[i];
     __syncthreads();
 
+    int P = 1;
+    while (P < c) P <<= 1;
     // bitonic sort of the candidates, best (largest key) first
     for (int size = 2; size <= P; size <<= 1) {
         for (int stride = size >> 1; stride > 0; stride >>= 1) {
@@ -207,6 +238,11 @@ hipError_t launch_merge(const TopkTileArgs& a, hipStream_t stream) {
     int pow2_k = 1;
     while (pow2_k < a.k) pow2_k <<= 1;
     const size_t lds = (static_cast<size_t>(pow2_k) + a.k) * sizeof(key64_t);
+    if (lds > 32 * 1024) {  // large k: raise the kernel's dynamic LDS limit (gfx950 has 160 KB per CU)
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(merge_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        if (e != hipSuccess) return e;
+    }
     hipLaunchKernelGGL(merge_kernel, dim3(a.rows, a.B), dim3(kTopkThreads), lds, stream, a, pow2_k);
     return hipGetLastError();
 }
