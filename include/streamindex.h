@@ -74,9 +74,9 @@ typedef struct {
 si_status si_plan_tiles(const si_dims* dims, int32_t m, int32_t k, si_mask_mode mask_mode,
                         size_t hbm_budget_bytes, si_plan* out);
 
-/* Bytes of workspace needed for a tiling: the running buffer [B,c_S,k] and the candidate
- * buffer [B,c_S,c_T] of 64-bit (score,index) keys, and two int32 counters per row (c_S, c_T
- * clamped to S, T).  0 on invalid arguments. */
+/* Bytes of workspace needed for a tiling: per query row of a tile a buffer of 2k + c_T
+ * 64-bit (score,index) keys (the running top-k plus the candidates of one key tile), an int32
+ * count and an fp32 threshold; B*c_S rows (c_S, c_T clamped to S, T).  0 on invalid arguments. */
 size_t si_workspace_bytes(const si_dims* dims, int32_t k, int32_t c_S, int32_t c_T);
 
 /* The whole step (Algorithm 2) with the tiling chosen by si_plan_tiles for
@@ -112,7 +112,7 @@ si_status si_score_tile(const void* q, const void* K, const float* w, const si_d
  * Row r's result is the top-min(k, legal[r]) of scores[r, 0:legal[r]] under the total order,
  * reached by streaming column tiles of c_T through the running buffer.
  *   out_idx device [R,k] int32, out_score device [R,k] f32.
- * workspace needs si_workspace_bytes({B=1, S=R, T=max(n_cols,k), ..}, k, c_S=R, c_T=k) bytes. */
+ * workspace needs si_workspace_bytes({B=1, S=R, T=n_cols, ..}, k, c_S=R, c_T) bytes. */
 si_status si_topk_from_scores(const float* scores, int32_t R, int32_t n_cols,
                               const int32_t* legal, int32_t k, int32_t c_T, int32_t* out_idx,
                               float* out_score, void* workspace, size_t workspace_bytes,
@@ -125,8 +125,9 @@ uint64_t si_materialize_bytes(const si_dims* dims);
 /* Per-kernel timing for benchmarks.  When enabled, every kernel launch made by the entry
  * points above is bracketed by HIP events on its stream.  si_profile_read synchronises
  * those events and returns, per kernel class, the summed duration in milliseconds and the
- * number of launches since the last reset.  Classes: 0 score tile, 1 select, 2 select+merge,
- * 3 write-out, 4 buffer init.  Not thread safe; meant for a single benchmarking thread. */
+ * number of launches since the last reset.  Classes: 0 score tile (with its fused filter),
+ * 1 filter of caller-supplied scores, 2 compaction (select + merge), 3 final sort + write-out,
+ * 4 buffer init.  Not thread safe; meant for a single benchmarking thread. */
 #define SI_PROFILE_CLASSES 5
 si_status si_profile_enable(int32_t on);
 si_status si_profile_reset(void);

@@ -20,7 +20,7 @@ SI_ERR_HIP = -4
 SI_MASK_NONE = 0
 SI_MASK_CAUSAL_BLOCK = 1
 SI_PROFILE_CLASSES = 5
-PROFILE_CLASS_NAMES = ("score_tile", "select", "merge", "writeout", "init")
+PROFILE_CLASS_NAMES = ("score_tile", "filter_scores", "compact", "finalize", "init")
 
 EXPORTS = (
     "si_plan_tiles", "si_workspace_bytes", "si_indexer_topk", "si_indexer_topk_tiled",

@@ -93,7 +93,6 @@ si_status check_dims(const si_dims* d, int32_t m, int32_t k, int mask_mode) {
     return SI_OK;
 }
 
-// The fused path keeps, per query row of a tile, k running keys and up to c_T candidates.
 size_t workspace_bytes_for(int64_t B, int64_t c_S, int64_t c_T, int64_t k) {
     return carve_workspace(nullptr, B * c_S, k, std::max<int64_t>(c_T, 1)).bytes;
 }
@@ -110,21 +109,22 @@ int64_t next_width(int64_t t0, int64_t c_T, int64_t k) {
 
 }  // namespace
 
-Workspace carve_workspace(void* base, int64_t rows_, int64_t k, int64_t cand_stride) {
-    Workspace ws;
+// Per query row of a tile: a key buffer of 2k + c_T slots (a row is cut back to k as soon as
+// it holds 2k, and one key tile adds at most c_T), a count and a threshold.
+RowBuffers carve_workspace(void* base, int64_t rows_, int64_t k, int64_t c_T) {
+    RowBuffers rb;
     const size_t rows = static_cast<size_t>(rows_);
+    rb.cap = static_cast<int32_t>(2 * k + c_T);
     size_t off = 0;
     char* p = static_cast<char*>(base);
-    ws.run_keys = reinterpret_cast<key64_t*>(p + off);
-    off = align_up(off + rows * static_cast<size_t>(k) * sizeof(key64_t), 256);
-    ws.cand_keys = reinterpret_cast<key64_t*>(p + off);
-    off = align_up(off + rows * static_cast<size_t>(cand_stride) * sizeof(key64_t), 256);
-    ws.run_count = reinterpret_cast<int32_t*>(p + off);
+    rb.keys = reinterpret_cast<key64_t*>(p + off);
+    off = align_up(off + rows * static_cast<size_t>(rb.cap) * sizeof(key64_t), 256);
+    rb.count = reinterpret_cast<int32_t*>(p + off);
     off = align_up(off + rows * sizeof(int32_t), 256);
-    ws.cand_count = reinterpret_cast<int32_t*>(p + off);
-    off = align_up(off + rows * sizeof(int32_t), 256);
-    ws.bytes = off;
-    return ws;
+    rb.theta = reinterpret_cast<float*>(p + off);
+    off = align_up(off + rows * sizeof(float), 256);
+    rb.bytes = off;
+    return rb;
 }
 
 }  // namespace si
@@ -196,15 +196,13 @@ si_status si_indexer_topk_tiled(const void* q, const void* K, const float* w,
     const si_dims d = *dims;
     c_S = std::min(c_S, d.S);
     c_T = std::min(c_T, d.T);
-    const Workspace ws = carve_workspace(workspace, static_cast<int64_t>(d.B) * c_S, k, c_T);
-    if (ws.bytes > workspace_bytes) return SI_ERR_WORKSPACE_TOO_SMALL;
+    const RowBuffers rb = carve_workspace(workspace, static_cast<int64_t>(d.B) * c_S, k, c_T);
+    if (rb.bytes > workspace_bytes) return SI_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t hs = static_cast<hipStream_t>(stream);
 
     for (int64_t s0 = 0; s0 < d.S; s0 += c_S) {
         const int32_t rows = static_cast<int32_t>(std::min<int64_t>(c_S, d.S - s0));
-        hipError_t e = timed(kProfInit, hs, [&] {
-            return launch_init_rows(ws.run_count, d.B * c_S, hs);
-        });
+        hipError_t e = timed(kProfInit, hs, [&] { return launch_init_rows(rb, d.B * c_S, hs); });
         if (e != hipSuccess) return hip_fail(e);
         // keys visible to the last query of this tile (Section 4.2); later key tiles are skipped
         int64_t t_hi = d.T;
@@ -213,22 +211,15 @@ si_status si_indexer_topk_tiled(const void* q, const void* K, const float* w,
             const int32_t width = static_cast<int32_t>(std::min<int64_t>(next_width(t0, c_T, k), d.T - t0));
             e = timed(kProfScore, hs, [&] {
                 return launch_score_filter(q, K, w, d, m, mask_mode, static_cast<int32_t>(s0),
-                                           static_cast<int32_t>(t0), rows, width, c_S, ws.run_keys,
-                                           ws.run_count, ws.cand_keys, ws.cand_count, k, c_T, hs);
+                                           static_cast<int32_t>(t0), rows, width, c_S, rb, hs);
             });
             if (e != hipSuccess) return hip_fail(e);
-            TopkTileArgs a{};
-            a.B = d.B; a.rows = rows; a.tile_rows = c_S;
-            a.k = k; a.cand_stride = c_T;
-            a.run_keys = ws.run_keys; a.run_count = ws.run_count;
-            a.cand_keys = ws.cand_keys; a.cand_count = ws.cand_count;
-            e = timed(kProfMerge, hs, [&] { return launch_merge(a, hs); });
+            e = timed(kProfMerge, hs, [&] { return launch_compact(rb, d.B, rows, c_S, k, 2 * k, hs); });
             if (e != hipSuccess) return hip_fail(e);
             t0 += width;
         }
         e = timed(kProfWriteout, hs, [&] {
-            return launch_writeout(ws.run_keys, ws.run_count, d.B, rows, c_S, k, d.S, s0, out_idx,
-                                   out_score, hs);
+            return launch_finalize(rb, d.B, rows, c_S, k, d.S, s0, out_idx, out_score, hs);
         });
         if (e != hipSuccess) return hip_fail(e);
     }
@@ -255,32 +246,21 @@ si_status si_topk_from_scores(const float* scores, int32_t R, int32_t n_cols,
     if (k > kMaxK) return SI_ERR_UNSUPPORTED_SHAPE;
     if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return SI_ERR_INVALID_ARG;
     c_T = std::min(c_T, n_cols);
-    // no score tile of our own here: the caller's matrix is read in place
-    const Workspace ws = carve_workspace(workspace, R, k, k);
-    if (ws.bytes > workspace_bytes) return SI_ERR_WORKSPACE_TOO_SMALL;
+    const RowBuffers rb = carve_workspace(workspace, R, k, c_T);
+    if (rb.bytes > workspace_bytes) return SI_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    hipError_t e = timed(kProfInit, hs, [&] { return launch_init_rows(ws.run_count, R, hs); });
+    hipError_t e = timed(kProfInit, hs, [&] { return launch_init_rows(rb, R, hs); });
     if (e != hipSuccess) return hip_fail(e);
     for (int64_t t0 = 0; t0 < n_cols; t0 += c_T) {
-        TopkTileArgs a{};
-        a.scores = scores;
-        a.B = 1; a.rows = R; a.tile_rows = R; a.tile_cols = n_cols;
-        a.s0 = 0; a.t0 = static_cast<int32_t>(t0);
-        a.width = static_cast<int32_t>(std::min<int64_t>(c_T, n_cols - t0));
-        a.col0 = static_cast<int32_t>(t0);
-        a.cand_stride = k;
-        a.T = n_cols; a.m = 1; a.mask_mode = SI_MASK_NONE; a.k = k;
-        a.legal_rows = legal;
-        a.run_keys = ws.run_keys; a.run_count = ws.run_count;
-        a.cand_keys = ws.cand_keys; a.cand_count = ws.cand_count;
-        e = timed(kProfSelect, hs, [&] { return launch_select(a, hs); });
+        const int32_t width = static_cast<int32_t>(std::min<int64_t>(c_T, n_cols - t0));
+        e = timed(kProfSelect, hs, [&] {
+            return launch_filter_scores(scores, R, n_cols, static_cast<int32_t>(t0), width, legal, rb, hs);
+        });
         if (e != hipSuccess) return hip_fail(e);
-        e = timed(kProfMerge, hs, [&] { return launch_merge(a, hs); });
+        e = timed(kProfMerge, hs, [&] { return launch_compact(rb, 1, R, R, k, 2 * k, hs); });
         if (e != hipSuccess) return hip_fail(e);
     }
-    e = timed(kProfWriteout, hs, [&] {
-        return launch_writeout(ws.run_keys, ws.run_count, 1, R, R, k, R, 0, out_idx, out_score, hs);
-    });
+    e = timed(kProfWriteout, hs, [&] { return launch_finalize(rb, 1, R, R, k, R, 0, out_idx, out_score, hs); });
     return e == hipSuccess ? SI_OK : hip_fail(e);
 }
 

@@ -17,11 +17,12 @@
 // Two outputs, chosen at compile time:
 //   dense  : the fp32 tile itself (entry point si_score_tile);
 //   filter : the per-tile mask (Section 5) and the first half of the per-tile select are
-//            applied in registers: only legal entries that beat the row's current k-th best
-//            score are appended, as 64-bit (score, ~index) keys, to the row's candidate list.
-//            An entry that does not beat the k-th best can never enter the final top-k
-//            (key tiles are visited in ascending index order, so on equal score the entry
-//            already held has the smaller index and wins, Section 4.1).
+//            applied in registers: only legal entries that beat the row's threshold (the k-th
+//            best score of an earlier prefix of the key axis) are appended, as 64-bit
+//            (score, ~index) keys, to the row's buffer.  An entry that does not beat it can
+//            never enter the final top-k: key tiles are visited in ascending index order, so
+//            on equal score the entry already held has the smaller index and wins
+//            (Section 4.1).  One wave owns one row, so the append needs no atomics.
 
 #include "si_internal.h"
 
@@ -37,21 +38,12 @@ constexpr int kScoreThreads = 64 * kQueriesPerBlock;
 // max(x, 0) on the bit pattern: negative floats (and -0) are negative integers.
 __device__ inline float relu(float x) { return __int_as_float(max(__float_as_int(x), 0)); }
 
-struct FilterArgs {
-    const key64_t* run_keys;   // [B*tile_rows, k]
-    const int32_t* run_count;  // [B*tile_rows]
-    key64_t* cand_keys;        // [B*tile_rows, cand_stride]
-    int32_t* cand_count;       // [B*tile_rows]
-    int32_t k;
-    int32_t cand_stride;
-};
-
 template <int D, int HB, bool FILTER>
 __global__ __launch_bounds__(kScoreThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void score_tile_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ K,
                        const float* __restrict__ w, int S, int H, int T, int m, int mask_mode,
                        int s0, int t0, int rows, int width, int tile_rows, int tile_cols,
-                       float* __restrict__ tile, FilterArgs f) {
+                       float* __restrict__ tile, RowBuffers rb) {
     constexpr int KS = D / 16;             // MFMA steps along d
     constexpr int kRowBytes = D * 2 + 16;  // LDS key row, padded by 16 B against bank conflicts
     constexpr int kPieces = D / 8;         // 16-byte pieces per key row
@@ -74,10 +66,7 @@ void score_tile_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ 
     // Section 4.2).  Uniform over the workgroup, so the early return is safe.
     const int r_last = min(rows, r_first + kQueriesPerBlock) - 1;
     const int n_keys = min(width, legal_count(s0 + r_last, T, m, mask_mode) - t0);
-    if (n_keys <= 0) {
-        if (FILTER && live && lane == 0) f.cand_count[ws_row] = 0;
-        return;
-    }
+    if (n_keys <= 0) return;
 
     // Query operand: head h = hb*32 + col, d = ks*16 + half*8 .. +8.  Addresses are clamped into
     // the problem instead of predicated: a wave whose row is past the tile edge recomputes the
@@ -101,15 +90,16 @@ void score_tile_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ 
         }
     }
 
-    // filter mode: this row's legal keys inside the tile, its current k-th best score, its list
+    // filter mode: this row's legal keys inside the tile, its threshold score, its buffer
     int row_keys = 0;
-    float theta = -__builtin_huge_valf();
+    float theta = 0.0f;
     key64_t* cand = nullptr;
     int n_cand = 0;
-    if (FILTER) {
-        row_keys = live ? min(width, legal_count(s0 + r, T, m, mask_mode) - t0) : 0;
-        if (live && f.run_count[ws_row] == f.k) theta = key_score(f.run_keys[ws_row * f.k + f.k - 1]);
-        cand = f.cand_keys + ws_row * f.cand_stride;
+    if (FILTER && live) {
+        row_keys = min(width, legal_count(s0 + r, T, m, mask_mode) - t0);
+        theta = rb.theta[ws_row];
+        n_cand = rb.count[ws_row];
+        cand = rb.keys + ws_row * rb.cap;
     }
 
     const __bf16* Kb = K + (static_cast<int64_t>(b) * T + t0) * D;
@@ -193,14 +183,14 @@ void score_tile_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ 
     }
 #undef SI_FETCH
 #undef SI_STASH
-    if (FILTER && live && lane == 0) f.cand_count[ws_row] = n_cand;
+    if (FILTER && live && lane == 0) rb.count[ws_row] = n_cand;
 }
 
 namespace {
 template <bool FILTER>
 hipError_t launch(const void* q, const void* K, const float* w, const si_dims& d, int32_t m,
                   int32_t mask_mode, int32_t s0, int32_t t0, int32_t rows, int32_t width,
-                  int32_t tile_rows, int32_t tile_cols, float* tile, const FilterArgs& f,
+                  int32_t tile_rows, int32_t tile_cols, float* tile, const RowBuffers& rb,
                   hipStream_t stream) {
     const dim3 grid((rows + kQueriesPerBlock - 1) / kQueriesPerBlock, d.B);
     const dim3 block(kScoreThreads);
@@ -210,7 +200,7 @@ hipError_t launch(const void* q, const void* K, const float* w, const si_dims& d
 #define SI_LAUNCH(DD, HH)                                                                        \
     hipLaunchKernelGGL((score_tile_kernel<DD, HH, FILTER>), grid, block, 0, stream, qp, Kp, w,  \
                        d.S, d.H_I, d.T, m, mask_mode, s0, t0, rows, width, tile_rows, tile_cols, \
-                       tile, f)
+                       tile, rb)
     if (d.D == 128 && HB == 2) SI_LAUNCH(128, 2);
     else if (d.D == 128 && HB == 1) SI_LAUNCH(128, 1);
     else if (d.D == 64 && HB == 2) SI_LAUNCH(64, 2);
@@ -228,16 +218,14 @@ hipError_t launch_score_tile(const void* q, const void* K, const float* w, const
                              int32_t width, int32_t tile_rows, int32_t tile_cols, float* tile,
                              hipStream_t stream) {
     return launch<false>(q, K, w, d, m, mask_mode, s0, t0, rows, width, tile_rows, tile_cols, tile,
-                         FilterArgs{}, stream);
+                         RowBuffers{}, stream);
 }
 
 hipError_t launch_score_filter(const void* q, const void* K, const float* w, const si_dims& d,
                                int32_t m, int32_t mask_mode, int32_t s0, int32_t t0, int32_t rows,
-                               int32_t width, int32_t tile_rows, const key64_t* run_keys,
-                               const int32_t* run_count, key64_t* cand_keys, int32_t* cand_count,
-                               int32_t k, int32_t cand_stride, hipStream_t stream) {
-    FilterArgs f{run_keys, run_count, cand_keys, cand_count, k, cand_stride};
-    return launch<true>(q, K, w, d, m, mask_mode, s0, t0, rows, width, tile_rows, 0, nullptr, f,
+                               int32_t width, int32_t tile_rows, const RowBuffers& rb,
+                               hipStream_t stream) {
+    return launch<true>(q, K, w, d, m, mask_mode, s0, t0, rows, width, tile_rows, 0, nullptr, rb,
                         stream);
 }
 

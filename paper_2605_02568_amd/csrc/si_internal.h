@@ -44,53 +44,38 @@ constexpr int kMaxK = 4096;
 constexpr int kMaxHeads = 64;
 constexpr int kQueriesPerBlock = 8;  // score kernel: one query per wave, 8 waves
 
-// Carve-up of the caller's workspace.
-struct Workspace {
-    key64_t* run_keys;    // [rows, k] sorted best first, run_count valid
-    key64_t* cand_keys;   // [rows, cand_stride] unsorted, cand_count valid
-    int32_t* run_count;   // [rows]
-    int32_t* cand_count;  // [rows]
+// Per-row state of the current query tile, carved from the caller's workspace.
+struct RowBuffers {
+    key64_t* keys;   // [rows, cap] unsorted
+    int32_t* count;  // [rows] keys held
+    float* theta;    // [rows] score an entry must beat to be appended (-inf until k are known)
+    int32_t cap;     // slots per row = 2k + c_T
     size_t bytes;
 };
-Workspace carve_workspace(void* base, int64_t rows, int64_t k, int64_t cand_stride);
+RowBuffers carve_workspace(void* base, int64_t rows, int64_t k, int64_t c_T);
 
 enum ProfileClass { kProfScore = 0, kProfSelect = 1, kProfMerge = 2, kProfWriteout = 3, kProfInit = 4 };
 
 // Kernel launchers (each enqueues exactly one kernel on `stream`).
+// Dense fp32 tile [B, tile_rows, tile_cols] of queries [s0, s0+rows) x keys [t0, t0+width).
 hipError_t launch_score_tile(const void* q, const void* K, const float* w, const si_dims& d,
                              int32_t m, int32_t mask_mode, int32_t s0, int32_t t0, int32_t rows,
                              int32_t width, int32_t tile_rows, int32_t tile_cols, float* tile,
                              hipStream_t stream);
-
-// scores row r of batch b: scores + (b*tile_rows + r)*tile_cols.  Query position of row r is
-// s0 + r when legal_rows == nullptr (legal count from the mask), else legal_rows[b*tile_rows+r]
-// is the row's legal count over the whole key axis.
-struct TopkTileArgs {
-    const float* scores;
-    int32_t B, rows, tile_rows, tile_cols;  // rows <= tile_rows live rows per batch
-    int32_t s0, t0, width;                  // key tile [t0, t0+width)
-    int32_t col0;                           // column of `scores` that holds key t0
-    int32_t cand_stride;                    // slots per row in cand_keys
-    int32_t T, m, mask_mode, k;
-    const int32_t* legal_rows;
-    key64_t* run_keys;
-    int32_t* run_count;
-    key64_t* cand_keys;
-    int32_t* cand_count;
-};
-// Score tile fused with the mask and the first half of the select: appends, per row, the
-// legal entries that beat the row's current k-th best to cand_keys and sets cand_count.
+// Score tile fused with the mask and the filter: appends, per row, the legal entries that beat
+// the row's threshold to the row's buffer (row index = b*tile_rows + r).
 hipError_t launch_score_filter(const void* q, const void* K, const float* w, const si_dims& d,
                                int32_t m, int32_t mask_mode, int32_t s0, int32_t t0, int32_t rows,
-                               int32_t width, int32_t tile_rows, const key64_t* run_keys,
-                               const int32_t* run_count, key64_t* cand_keys, int32_t* cand_count,
-                               int32_t k, int32_t cand_stride, hipStream_t stream);
-hipError_t launch_init_rows(int32_t* run_count, int32_t n, hipStream_t stream);
-hipError_t launch_select(const TopkTileArgs& a, hipStream_t stream);
-hipError_t launch_merge(const TopkTileArgs& a, hipStream_t stream);
-hipError_t launch_writeout(const key64_t* run_keys, const int32_t* run_count, int32_t B,
-                           int32_t rows, int32_t tile_rows, int32_t k, int64_t out_batch_stride,
-                           int64_t out_row0, int32_t* out_idx, float* out_score,
-                           hipStream_t stream);
+                               int32_t width, int32_t tile_rows, const RowBuffers& rb,
+                               hipStream_t stream);
+hipError_t launch_init_rows(const RowBuffers& rb, int32_t n, hipStream_t stream);
+hipError_t launch_filter_scores(const float* scores, int32_t R, int32_t n_cols, int32_t t0,
+                                int32_t width, const int32_t* legal_rows, const RowBuffers& rb,
+                                hipStream_t stream);
+hipError_t launch_compact(const RowBuffers& rb, int32_t B, int32_t rows, int32_t tile_rows, int32_t k,
+                          int32_t trigger, hipStream_t stream);
+hipError_t launch_finalize(const RowBuffers& rb, int32_t B, int32_t rows, int32_t tile_rows, int32_t k,
+                           int64_t out_batch_stride, int64_t out_row0, int32_t* out_idx,
+                           float* out_score, hipStream_t stream);
 
 }  // namespace si

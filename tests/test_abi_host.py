@@ -30,9 +30,9 @@ def test_strerror_and_sizes():
         assert P.si_strerror(code) not in ("ok", "unknown status")
     # Section 1: 256 GB at S=65536 with H_I=64, T=S/4
     assert P.si_materialize_bytes(1, 65536, 64, 128, 16384) == 256 * GiB
-    # workspace = running buffer [c_S,k] + candidate buffer [c_S,c_T] of u64 keys + counters
+    # workspace = per row (2k + c_T) u64 keys + a count + a threshold
     ws = P.si_workspace_bytes(1, 1 << 20, 64, 128, 1 << 18, 1024, 2048, 8192)
-    expect = 2048 * 8192 * 8 + 2048 * 1024 * 8 + 2 * 2048 * 4
+    expect = 2048 * (2 * 1024 + 8192) * 8 + 2 * 2048 * 4
     assert expect <= ws <= expect + 5 * 256
     assert P.si_workspace_bytes(1, 100, 4, 32, 25, 16, 4096, 4096) == \
         P.si_workspace_bytes(1, 100, 4, 32, 25, 16, 100, 25)  # clamped to the problem

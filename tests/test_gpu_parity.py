@@ -134,7 +134,7 @@ def test_topk_from_scores_is_bit_exact(oracle, name):
             _say(f"topk_from_scores {name} k={k} c_T={c_T} legal={'yes' if lg is not None else 'no'}")
             out_idx = torch.full((R, k), -7, dtype=torch.int32, device=DEV)
             out_score = torch.full((R, k), 9.0, dtype=torch.float32, device=DEV)
-            ws = _workspace(P.si_workspace_bytes(1, R, 1, 32, max(n, k), k, R, k))
+            ws = _workspace(P.si_workspace_bytes(1, R, 1, 32, n, k, R, c_T))
             lgd = None if lg is None else torch.from_numpy(lg).to(DEV)
             P.si_topk_from_scores(scd, lgd, k, c_T, out_idx, out_score, ws)
             torch.cuda.synchronize()
