@@ -9,8 +9,12 @@
 //     8 bf16.  Keys are the N side, 32 per MFMA, read from LDS.
 //   - the 32x32 result puts one key per lane column (lane & 31) and 16 heads per lane, so the
 //     head sum is 16 in-lane FMAs per head block plus one exchange between lane and lane^32.
-//   - a workgroup is 8 waves = 8 consecutive queries sharing each staged block of keys; the
-//     next block is prefetched into registers while the current one is being used.
+//   - a workgroup is 8 waves = 8 consecutive queries sharing each staged block of 128 keys.
+//     Key blocks travel HBM/L2 -> LDS directly (global_load_lds, no register round trip) into
+//     a ring of three buffers, two blocks ahead of the one being multiplied.
+//   - the loop is a software pipeline over 32-key sub-blocks: MFMAs of sub-block g, epilogue
+//     of sub-block g-1 and LDS reads for sub-block g+1 are interleaved instruction by
+//     instruction, so the matrix pipe, the vector ALU and the LDS work at the same time.
 // Every (query, key) score is produced by the same instruction sequence wherever the pair
 // falls in a tile, which is what makes results independent of the tiling.
 //
@@ -32,8 +36,11 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kKeyChunk = 128;  // keys staged in LDS per step
-constexpr int kScoreThreads = 64 * kQueriesPerBlock;
+constexpr int kWaves = 8;            // waves per workgroup, one query each
+constexpr int kQB = kWaves;          // queries per workgroup
+constexpr int kKeyChunk = 128;       // keys per LDS buffer
+constexpr int kScoreThreads = 64 * kWaves;
+constexpr int kLdsBuffers = 3;
 
 // max(x, 0) on the bit pattern: negative floats (and -0) are negative integers.
 __device__ inline float relu(float x) { return __int_as_float(max(__float_as_int(x), 0)); }
@@ -45,26 +52,35 @@ void score_tile_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ 
                        int s0, int t0, int rows, int width, int tile_rows, int tile_cols,
                        float* __restrict__ tile, RowBuffers rb) {
     constexpr int KS = D / 16;             // MFMA steps along d
-    constexpr int kRowBytes = D * 2 + 16;  // LDS key row, padded by 16 B against bank conflicts
+    constexpr int EPG = 16 * HB / KS;      // epilogue elements handled next to one MFMA step
+    static_assert(16 * HB % KS == 0, "epilogue elements must split evenly over the MFMA steps");
+    // LDS key rows are unpadded (2*D bytes); the 16-byte pieces of a row are XOR-swizzled so
+    // that the 16 lanes served together by one ds_read_b128 hit 16 different bank groups:
+    // piece p of row r sits in slot p ^ swz(r), swz(r) = (r / rows per 256 B) mod pieces per row.
+    constexpr int kRowBytes = D * 2;
     constexpr int kPieces = D / 8;         // 16-byte pieces per key row
+    constexpr int kRowsPer256 = 256 / kRowBytes;
     constexpr int kBufBytes = kKeyChunk * kRowBytes;
-    constexpr int kLoads = kKeyChunk * kPieces / kScoreThreads;  // 16-byte loads per thread per chunk
-    static_assert(kKeyChunk * kPieces % kScoreThreads == 0, "chunk must split evenly over the threads");
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * kBufBytes];
+    constexpr int kRowsPerLoad = 64 / kPieces;  // key rows covered by one wave-wide 1 KiB load
+    constexpr int kLoads = kKeyChunk / kRowsPerLoad / kWaves;  // loads per wave per chunk
+    static_assert(kKeyChunk % (kRowsPerLoad * kWaves) == 0, "chunk must split evenly over the waves");
+    static_assert(kKeyChunk == 128, "the pipelined loop is written for 4 sub-blocks per chunk");
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[kLdsBuffers * kBufBytes];
 
-    const int wave = threadIdx.x >> 6;
+    // wave-uniform values (row, threshold, counters, pointers) live in scalar registers
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int col = lane & 31;
     const int half = lane >> 5;
     const int b = blockIdx.y;
-    const int r_first = blockIdx.x * kQueriesPerBlock;
+    const int r_first = blockIdx.x * kQB;
     const int r = r_first + wave;  // row inside the tile
     const bool live = r < rows;
     const int64_t ws_row = static_cast<int64_t>(b) * tile_rows + r;
 
     // Keys of this tile that the last query of the workgroup may see (causal block mask,
     // Section 4.2).  Uniform over the workgroup, so the early return is safe.
-    const int r_last = min(rows, r_first + kQueriesPerBlock) - 1;
+    const int r_last = min(rows, r_first + kQB) - 1;
     const int n_keys = min(width, legal_count(s0 + r_last, T, m, mask_mode) - t0);
     if (n_keys <= 0) return;
 
@@ -85,8 +101,10 @@ void score_tile_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ 
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const int hh = hb * 32 + 8 * (j >> 2) + 4 * half + (j & 3);
-            const float wv = w[qrow * H + min(hh, H - 1)];
-            wr[hb][j] = hh < H ? wv : 0.0f;
+            float wv = w[qrow * H + min(hh, H - 1)];
+            wv = hh < H ? wv : 0.0f;
+            asm volatile("" : "+v"(wv));  // keep the masked weight in a register for the whole sweep
+            wr[hb][j] = wv;
         }
     }
 
@@ -101,89 +119,123 @@ void score_tile_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ 
         n_cand = rb.count[ws_row];
         cand = rb.keys + ws_row * rb.cap;
     }
-
-    const __bf16* Kb = K + (static_cast<int64_t>(b) * T + t0) * D;
     float* out_row = tile + ws_row * tile_cols;
+    const __bf16* Kb = K + (static_cast<int64_t>(b) * T + t0) * D;
 
-    u32x4 pre[kLoads];
-#define SI_FETCH(KC0)                                                                              \
+    // Global -> LDS without a register round trip: each wave-wide load writes 1 KiB of LDS
+    // (lane l to byte l*16 of the block); the lane picks the global piece that belongs there.
+    typedef __attribute__((address_space(3))) void lds_void;
+    typedef __attribute__((address_space(1))) const void gbl_void;
+#define SI_FETCH(KC0, BUFOFF)                                                                      \
     _Pragma("unroll") for (int i = 0; i < kLoads; ++i) {                                            \
-        const int p = threadIdx.x + i * kScoreThreads;                                              \
-        const int row = p / kPieces, c = p % kPieces;                                               \
+        const int blk = wave * kLoads + i;                   /* 1 KiB block inside the chunk */     \
+        const int row = blk * kRowsPerLoad + lane / kPieces; /* key row inside the chunk */         \
+        const int piece = (lane % kPieces) ^ ((row / kRowsPer256) % kPieces);                       \
         const int key = min((KC0) + row, width - 1); /* rows past the edge repeat the last key */   \
-        pre[i] = *reinterpret_cast<const u32x4*>(Kb + static_cast<int64_t>(key) * D + c * 8);       \
-    }
-#define SI_STASH(BUF)                                                                              \
-    _Pragma("unroll") for (int i = 0; i < kLoads; ++i) {                                            \
-        const int p = threadIdx.x + i * kScoreThreads;                                              \
-        const int row = p / kPieces, c = p % kPieces;                                               \
-        *reinterpret_cast<u32x4*>(lds + (BUF) * kBufBytes + row * kRowBytes + c * 16) = pre[i];     \
+        const __bf16* src = Kb + static_cast<int64_t>(key) * D + piece * 8;                         \
+        __builtin_amdgcn_global_load_lds((gbl_void*)(src),                                          \
+            (lds_void*)(lds + (BUFOFF) + blk * 1024), 16, 0, 0);                                    \
     }
 
-    SI_FETCH(0)
-    SI_STASH(0)
-    // every prologue load has landed before the loop, so no wait on them is needed inside it
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    // This lane's byte offset, inside a 32-key sub-block, of the operand for MFMA step ks.
+    const int swz = (col / kRowsPer256) % kPieces;
+    int koff[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) koff[ks] = col * kRowBytes + (((ks * 2 + half) ^ swz) * 16);
+#define SI_KREAD(BYTEOFF, KSTEP) \
+    (*reinterpret_cast<const bf16x8*>(lds + (BYTEOFF) + koff[KSTEP]))
+
+    // Chunks 0 and 1 in flight; chunk 0 must have landed before its first read.
+    int off_cur = 0, off_next = kBufBytes, off_nn = 2 * kBufBytes;  // LDS buffers: being read, next, filling
+    SI_FETCH(0, off_cur)
+    SI_FETCH(kKeyChunk, off_next)
+    __builtin_amdgcn_s_waitcnt(0x0F70 | kLoads);  // vmcnt(kLoads): everything but chunk 1 has landed
     __syncthreads();
 
-    int buf = 0;
-    for (int kc0 = 0; kc0 < n_keys; kc0 += kKeyChunk, buf ^= 1) {
-        const bool more = kc0 + kKeyChunk < n_keys;
-        if (more) { SI_FETCH(kc0 + kKeyChunk) }
-        const unsigned char* base = lds + buf * kBufBytes + col * kRowBytes + half * 16;
-        float res[kKeyChunk / 64];  // lane l: score of key kc0 + i*64 + l
+    bf16x8 bq[KS];  // key operand of the sub-block about to be multiplied
 #pragma unroll
-        for (int sb = 0; sb < kKeyChunk / 32; ++sb) {
-            floatx16 acc[HB];
+    for (int ks = 0; ks < KS; ++ks) bq[ks] = SI_KREAD(off_cur, ks);
+
+    // Software pipeline, one step per 32-key sub-block: the MFMAs of sub-block g fill one
+    // accumulator set while the ReLU / weight / head-sum epilogue drains the other one (sub-block
+    // g-1), and the key operand of sub-block g+1 is read from LDS into the registers the MFMAs
+    // have just consumed.  The scheduling barriers pin this interleaving: per MFMA step, HB MFMAs,
+    // EPG epilogue elements, one LDS read.
+    floatx16 accA[HB], accB[HB];
+    const floatx16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-            for (int hb = 0; hb < HB; ++hb)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) acc[hb][j] = 0.0f;
-            const unsigned char* krow = base + sb * 32 * kRowBytes;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const bf16x8 kv = *reinterpret_cast<const bf16x8*>(krow + ks * 32);
-#pragma unroll
-                for (int hb = 0; hb < HB; ++hb)
-                    acc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[hb][ks], kv, acc[hb], 0, 0, 0);
-            }
-            // ReLU, weight, head sum: fixed order hb, j; then the two lane halves.
-            float s = 0.0f;
-#pragma unroll
-            for (int hb = 0; hb < HB; ++hb)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) s = fmaf(wr[hb][j], relu(acc[hb][j]), s);
-            s += __shfl_xor(s, 32);
-            // even sub-blocks stay in the low half-wave, odd ones in the high half
-            if ((sb & 1) == 0) res[sb >> 1] = s;
-            else res[sb >> 1] = half ? s : res[sb >> 1];
-        }
-        if (more) { SI_STASH(buf ^ 1) }
-        if (FILTER) {
-#pragma unroll
-            for (int i = 0; i < kKeyChunk / 64; ++i) {
-                const int key = kc0 + i * 64 + lane;
-                const bool keep = key < row_keys && res[i] > theta;
-                const unsigned long long mask = __ballot(keep);
-                if (mask != 0ull) {
-                    const int below = __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(mask >> 32),
-                                      __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(mask), 0u));
-                    if (keep) cand[n_cand + below] = make_key(res[i], static_cast<uint32_t>(t0 + key));
-                    n_cand += __popcll(mask);
-                }
-            }
-        } else if (live) {
-#pragma unroll
-            for (int i = 0; i < kKeyChunk / 64; ++i) {
-                const int key = kc0 + i * 64 + lane;
-                if (key < n_keys) out_row[key] = res[i];
-            }
-        }
-        __syncthreads();
+    for (int hb = 0; hb < HB; ++hb) accB[hb] = zero16;
+#define SI_STEP(CUR, PREV, OUT, NEXT_BYTEOFF)                                                      \
+    {                                                                                               \
+        float s_ = 0.0f;                                                                            \
+        _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                         \
+            _Pragma("unroll") for (int hb = 0; hb < HB; ++hb)                                       \
+                CUR[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[hb][ks], bq[ks],                \
+                                                                  ks == 0 ? zero16 : CUR[hb], 0, 0, 0); \
+            _Pragma("unroll") for (int e = ks * EPG; e < (ks + 1) * EPG; ++e)                       \
+                s_ = fmaf(wr[e / 16][e % 16], relu(PREV[e / 16][e % 16]), s_);                      \
+            bq[ks] = SI_KREAD(NEXT_BYTEOFF, ks);                                                    \
+            __builtin_amdgcn_sched_barrier(0);                                                      \
+        }                                                                                           \
+        OUT = s_ + __shfl_xor(s_, 32);                                                              \
     }
+    // 64 finished scores (lane l holds key KEY0 + l): append the kept ones / store the tile row.
+#define SI_EMIT(VAL, KEY0)                                                                         \
+    {                                                                                               \
+        const int key = (KEY0) + lane;                                                              \
+        if (FILTER) {                                                                               \
+            const bool keep = key >= 0 && key < row_keys && (VAL) > theta;                          \
+            const unsigned long long mask = __ballot(keep);                                         \
+            if (mask != 0ull) {                                                                     \
+                const int below = __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(mask >> 32),      \
+                                  __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(mask), 0u));      \
+                if (keep) cand[n_cand + below] = make_key((VAL), static_cast<uint32_t>(t0 + key));  \
+                n_cand += __popcll(mask);                                                           \
+            }                                                                                       \
+        } else if (live && key >= 0 && key < n_keys) {                                              \
+            out_row[key] = (VAL);                                                                   \
+        }                                                                                           \
+    }
+
+    float r_even = 0.0f;  // epilogue result of the last even sub-block, waiting for its odd partner
+    int kc0 = 0;
+    for (; kc0 < n_keys; kc0 += kKeyChunk) {
+        // Chunk kc0/128 + 2 starts its trip to LDS.  Issued unconditionally (addresses are clamped,
+        // the buffer is unused if the chunk does not exist) so that the vmcnt arithmetic below holds.
+        SI_FETCH(kc0 + 2 * kKeyChunk, off_nn)
+        float sp, s0v, s1v, s2v;
+        SI_STEP(accA, accB, sp, off_cur + 1 * 32 * kRowBytes)
+        SI_STEP(accB, accA, s0v, off_cur + 2 * 32 * kRowBytes)
+        SI_STEP(accA, accB, s1v, off_cur + 3 * 32 * kRowBytes)
+        // The next chunk must be in LDS, and visible to every wave, before its first read below.
+        __builtin_amdgcn_s_waitcnt(0x0F70 | kLoads);  // vmcnt(kLoads): only the newest chunk may be in flight
+        __syncthreads();
+        SI_STEP(accB, accA, s2v, off_next)
+        // even sub-blocks stay in the low half-wave, odd ones in the high half
+        const float res_prev = half ? sp : r_even;   // keys kc0 - 64 + lane (previous chunk)
+        const float res_cur = half ? s1v : s0v;      // keys kc0 + lane
+        r_even = s2v;
+        if (!FILTER || __ballot((res_prev > theta) | (res_cur > theta)) != 0ull) {
+            SI_EMIT(res_prev, kc0 - 64)
+            SI_EMIT(res_cur, kc0)
+        }
+        const int t_ = off_cur; off_cur = off_next; off_next = off_nn; off_nn = t_;
+    }
+    {   // drain: the last sub-block's epilogue and the last 64 scores
+        float s_ = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 16 * HB; ++e) s_ = fmaf(wr[e / 16][e % 16], relu(accB[e / 16][e % 16]), s_);
+        const float sp = s_ + __shfl_xor(s_, 32);
+        const float res_prev = half ? sp : r_even;
+        SI_EMIT(res_prev, kc0 - 64)
+    }
+#undef SI_STEP
+#undef SI_EMIT
 #undef SI_FETCH
-#undef SI_STASH
+#undef SI_KREAD
     if (FILTER && live && lane == 0) rb.count[ws_row] = n_cand;
+    // loads of chunks past the end may still be in flight: let them land before the LDS is released
+    __builtin_amdgcn_s_waitcnt(0x0F70);
 }
 
 namespace {
@@ -192,7 +244,7 @@ hipError_t launch(const void* q, const void* K, const float* w, const si_dims& d
                   int32_t mask_mode, int32_t s0, int32_t t0, int32_t rows, int32_t width,
                   int32_t tile_rows, int32_t tile_cols, float* tile, const RowBuffers& rb,
                   hipStream_t stream) {
-    const dim3 grid((rows + kQueriesPerBlock - 1) / kQueriesPerBlock, d.B);
+    const dim3 grid((rows + kQB - 1) / kQB, d.B);
     const dim3 block(kScoreThreads);
     const __bf16* qp = static_cast<const __bf16*>(q);
     const __bf16* Kp = static_cast<const __bf16*>(K);

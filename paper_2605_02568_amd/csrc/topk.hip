@@ -23,83 +23,142 @@ namespace si {
 
 constexpr int kTopkThreads = 256;
 
-constexpr int kHistCopies = kTopkThreads / 64;  // one histogram per wave: less atomic contention
+constexpr int kRowWaves = kTopkThreads / 64;  // compaction / finalize: one wave per query row
+constexpr int kKeysInFlight = 16;             // global loads a lane issues before it uses them
 
-struct SelectShared {
-    int hist[kHistCopies][256];
-    int tmp;
-    int digit, need, bin;
+// ---- wave-level selection -----------------------------------------------------------------
+// One wave works on one row without workgroup barriers: its 64 lanes stream the row's keys from
+// global memory (the row buffer is L2 resident), build a 256-bin histogram in the wave's own
+// slice of LDS, and walk the bins with a wave prefix sum.
+
+// A row's keys as seen by one wave.  Lane l is responsible for keys l, l+64, l+128, ...
+// RegKeys holds them in registers (rows of up to 64*R keys: read from memory once);
+// StreamKeys re-reads them from global memory on every sweep (any length).
+template <int R>
+struct RegKeys {
+    key64_t kb[R];
+    int n;
+    __device__ inline void load(const key64_t* buf, int n_) {
+        n = n_;
+        const int lane = threadIdx.x & 63;
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            const int j = lane + 64 * i;
+            kb[i] = j < n ? buf[j] : 0ull;
+        }
+    }
+    // f(key, valid, first_lane_index): called for successive blocks of 64 keys, in key order
+    template <typename F>
+    __device__ inline void sweep(F&& f) const {
+        const int lane = threadIdx.x & 63;
+#pragma unroll
+        for (int i = 0; i < R; ++i) f(kb[i], lane + 64 * i < n);
+    }
 };
 
-__device__ inline int block_sum(int v, int* s_scratch) {
-    // wave reduce, then one LDS atomic per wave
+struct StreamKeys {
+    const key64_t* buf;
+    int n;
+    template <typename F>
+    __device__ inline void sweep(F&& f) const {
+        const int lane = threadIdx.x & 63;
+        // several keys per lane in flight at a time: latency is what matters
+        for (int base = 0; base < n; base += 64 * kKeysInFlight) {
+            key64_t kb[kKeysInFlight];
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
-    if (threadIdx.x == 0) *s_scratch = 0;
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) atomicAdd(s_scratch, v);
-    __syncthreads();
-    const int total = *s_scratch;
-    __syncthreads();
-    return total;
-}
+            for (int i = 0; i < kKeysInFlight; ++i) {
+                const int j = base + 64 * i + lane;
+                kb[i] = j < n ? buf[j] : 0ull;
+            }
+#pragma unroll
+            for (int i = 0; i < kKeysInFlight; ++i) f(kb[i], base + 64 * i + lane < n);
+        }
+    }
+};
 
-// Threshold key `thr` such that exactly k of the n keys produced by fetch(j), j in [0,n),
-// that are > floor satisfy key >= thr.  Requires more than k such keys.  All threads of the
-// workgroup call it with the same arguments.
-template <typename Fetch>
-__device__ inline key64_t radix_kth(Fetch fetch, int n, key64_t floor_key, int k, SelectShared& sh) {
-    const int tid = threadIdx.x;
+// Threshold key `thr` and count `kept` such that exactly `kept` of the row's n distinct keys
+// are >= thr, with k <= kept <= max(k, limit).  MSB-first radix descent, 8 bits per pass; it
+// stops as soon as the bin holding the k-th largest key is small enough for `kept` to respect
+// the limit (limit == k: exact selection).  Requires n > k.  Wave-uniform arguments.
+template <typename Keys>
+__device__ inline key64_t wave_radix_kth(const Keys& keys, int k, int limit, int* hist, int* kept) {
+    const int lane = threadIdx.x & 63;
     key64_t prefix = 0ull;
     int need = k;
+    int bin = 0;
     for (int shift = 56; shift >= 0; shift -= 8) {
 #pragma unroll
-        for (int cpy = 0; cpy < kHistCopies; ++cpy) sh.hist[cpy][tid] = 0;
-        __syncthreads();
-        for (int j = tid; j < n; j += kTopkThreads) {
-            const key64_t key = fetch(j);
-            const bool in_prefix = (shift == 56) || ((key >> (shift + 8)) == (prefix >> (shift + 8)));
-            if (key > floor_key && in_prefix) atomicAdd(&sh.hist[tid >> 6][(key >> shift) & 255ull], 1);
+        for (int i = 0; i < 4; ++i) hist[lane + 64 * i] = 0;
+        __builtin_amdgcn_wave_barrier();
+        if (shift >= 32) {
+            // digits of the score word: 32-bit arithmetic on the high half of the key
+            const int sh = shift - 32;
+            const uint32_t want = sh == 24 ? 0u : static_cast<uint32_t>(prefix >> 32) >> (sh + 8);
+            keys.sweep([&](key64_t key, bool valid) {
+                const uint32_t hi = static_cast<uint32_t>(key >> 32);
+                const bool in_prefix = (sh == 24) || ((hi >> (sh + 8)) == want);
+                if (valid && in_prefix) atomicAdd(&hist[(hi >> sh) & 255u], 1);
+            });
+        } else {
+            // equal scores: digits of the index word
+            const key64_t want = prefix >> (shift + 8);
+            keys.sweep([&](key64_t key, bool valid) {
+                const bool in_prefix = (key >> (shift + 8)) == want;
+                if (valid && in_prefix) atomicAdd(&hist[(key >> shift) & 255ull], 1);
+            });
         }
-        __syncthreads();
-        if (tid < 64) {
-            // Wave 0 walks the bins from the top: lane l owns bins 255-4l .. 252-4l.  A wave
-            // prefix sum locates the lane, then the bin, where the running count reaches `need`.
-            int h[4];
+        __builtin_amdgcn_wave_barrier();
+        // Lane l owns bins 255-4l .. 252-4l (walking down from the top bin).
+        int h[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                h[j] = 0;
+        for (int j = 0; j < 4; ++j) h[j] = hist[255 - 4 * lane - j];
+        __builtin_amdgcn_wave_barrier();
+        const int local = h[0] + h[1] + h[2] + h[3];
+        int incl = local;
 #pragma unroll
-                for (int cpy = 0; cpy < kHistCopies; ++cpy) h[j] += sh.hist[cpy][255 - 4 * tid - j];
-            }
-            const int local = h[0] + h[1] + h[2] + h[3];
-            int incl = local;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const int up = __shfl_up(incl, off);
-                if (tid >= off) incl += up;
-            }
-            int cum = incl - local;  // keys in bins above this lane's
-            if (cum < need && need <= incl) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    if (cum < need && need <= cum + h[j]) {
-                        sh.digit = 255 - 4 * tid - j;
-                        sh.need = need - cum;
-                        sh.bin = h[j];
-                    }
-                    cum += h[j];
-                }
-            }
+        for (int off = 1; off < 64; off <<= 1) {
+            const int up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
         }
-        __syncthreads();
-        prefix |= static_cast<key64_t>(sh.digit) << shift;
-        need = sh.need;
-        const bool whole_bin = (sh.bin == need);
-        __syncthreads();
-        if (whole_bin) break;  // every key of this bin is kept: prefix is the threshold
+        int cum = incl - local;  // keys in bins above this lane's
+        const bool crossing = cum < need && need <= incl;  // true in exactly one lane
+        int digit = 0, new_need = 0, new_bin = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (crossing && cum < need && need <= cum + h[j]) {
+                digit = 255 - 4 * lane - j;
+                new_need = need - cum;
+                new_bin = h[j];
+            }
+            cum += h[j];
+        }
+        const int src = __builtin_ctzll(__ballot(crossing));
+        digit = __shfl(digit, src);
+        need = __shfl(new_need, src);
+        bin = __shfl(new_bin, src);
+        prefix |= static_cast<key64_t>(digit) << shift;
+        // keys >= prefix: the (k - need) in higher bins plus this whole bin
+        if (k - need + bin <= limit) break;
     }
+    *kept = k - need + bin;
     return prefix;
+}
+
+// Writes the row's keys >= thr to dst[0, ...) in key order (dst may be the row buffer itself:
+// a block of keys is always read before anything at or behind it is written).  `cap` bounds
+// the writes.  Returns how many were written.
+template <typename Keys>
+__device__ inline int wave_keep(const Keys& keys, key64_t thr, key64_t* dst, int cap) {
+    int pos = 0;
+    keys.sweep([&](key64_t key, bool valid) {
+        const bool keep = valid && key >= thr;
+        const unsigned long long mask = __ballot(keep);
+        const int below = __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(mask >> 32),
+                          __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(mask), 0u));
+        if (keep && pos + below < cap) dst[pos + below] = key;
+        pos += __popcll(mask);
+    });
+    return pos;
 }
 
 // Dense-score front end (entry point si_topk_from_scores): appends the legal entries of one
@@ -128,100 +187,99 @@ __global__ __launch_bounds__(kTopkThreads) void filter_scores_kernel(
     if (tid == 0) rb.count[row] = c0 + s_cnt;
 }
 
-constexpr int kStageKeys = 4096;  // buffers up to this long are staged in LDS for the selection
 
-// Keeps exactly the k best of a row's n > k buffered keys in s_keep[0,k) (any order) and
-// returns the smallest kept key.  s_stage: kStageKeys slots of LDS; the radix passes read the
-// keys from there when they fit, else from global memory.  All threads of the workgroup call it.
-__device__ inline key64_t keep_top_k(const key64_t* buf, int n, int k, key64_t* s_keep,
-                                     key64_t* s_stage, SelectShared& sh, key64_t* s_min) {
-    const key64_t* src = buf;
-    if (n <= kStageKeys) {
-        for (int j = threadIdx.x; j < n; j += kTopkThreads) s_stage[j] = buf[j];
-        __syncthreads();
-        src = s_stage;
-    }
-    auto fetch = [&](int j) { return src[j]; };
-    const key64_t thr = radix_kth(fetch, n, 0ull, k, sh);
-    if (threadIdx.x == 0) {
-        sh.tmp = 0;
-        *s_min = ~0ull;
-    }
-    __syncthreads();
-    for (int j = threadIdx.x; j < n; j += kTopkThreads) {
-        const key64_t key = src[j];
-        if (key >= thr) {
-            const int pos = atomicAdd(&sh.tmp, 1);
-            if (pos < k) s_keep[pos] = key;  // pos < k always holds; the guard keeps a slip in bounds
-            atomicMin(s_min, key);
-        }
-    }
-    __syncthreads();
-    return *s_min;
-}
+__host__ __device__ inline int compact_limit(int k) { return k + k / 4; }
+constexpr int kCompactRegKeys = 48;   // compaction keeps rows of up to 3072 keys in registers
+constexpr int kFinalizeRegKeys = 32;  // finalize: rows of up to 2048 keys
 
 // Merge step, done lazily: a row's buffer holds the k best keys of an earlier prefix plus
-// everything appended since.  Once it holds at least `trigger` keys it is cut back to its k
-// best and the row's threshold becomes the score of the k-th of them.
+// everything appended since.  Once it holds at least `trigger` keys it is cut back to its best
+// k .. 1.25k keys (an exact cut is only needed at the very end) and the row's threshold is
+// raised to the score below which everything was dropped.  One wave per row.
 __global__ __launch_bounds__(kTopkThreads) void compact_kernel(RowBuffers rb, int rows, int tile_rows,
                                                                int k, int trigger) {
-    extern __shared__ key64_t s_keep[];  // [k] kept keys, then [kStageKeys] staging
-    __shared__ SelectShared sh;
-    __shared__ key64_t s_min;
-    const int64_t row = static_cast<int64_t>(blockIdx.y) * tile_rows + blockIdx.x;
-    (void)rows;
-    const int c = rb.count[row];
-    if (c < trigger) return;
-    key64_t* buf = rb.keys + row * rb.cap;
-    const key64_t kth = keep_top_k(buf, c, k, s_keep, s_keep + k, sh, &s_min);
-    for (int i = threadIdx.x; i < k; i += kTopkThreads) buf[i] = s_keep[i];
-    if (threadIdx.x == 0) {
-        rb.count[row] = k;
-        rb.theta[row] = key_score(kth);
+    __shared__ int s_hist[kRowWaves][256];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    {
+        const int r = blockIdx.x * kRowWaves + wave;
+        if (r >= rows) return;
+        const int64_t row = static_cast<int64_t>(blockIdx.y) * tile_rows + r;
+        const int c = rb.count[row];
+        if (c < trigger) return;  // most rows need nothing on most calls
+        key64_t* buf = rb.keys + row * rb.cap;
+        int kept = 0;
+        key64_t thr;
+        if (c <= 64 * kCompactRegKeys) {  // the usual case: one read of the row
+            RegKeys<kCompactRegKeys> keys;
+            keys.load(buf, c);
+            thr = wave_radix_kth(keys, k, compact_limit(k), s_hist[wave], &kept);
+            wave_keep(keys, thr, buf, rb.cap);
+        } else {
+            const StreamKeys keys{buf, c};
+            thr = wave_radix_kth(keys, k, compact_limit(k), s_hist[wave], &kept);
+            wave_keep(keys, thr, buf, rb.cap);
+        }
+        if ((threadIdx.x & 63) == 0) {
+            rb.count[row] = kept;
+            rb.theta[row] = fmaxf(rb.theta[row], key_score(thr));  // the cut may be coarser than the old threshold
+        }
     }
 }
 
-// After the last key tile: final cut to k, sort best first, decode, pad (Section 4.2).
+// After the last key tile: final exact cut to k, sort best first, decode, pad (Section 4.2).
+// One wave per row; the sort is a bitonic network over the wave's own slice of LDS.
 __global__ __launch_bounds__(kTopkThreads) void finalize_kernel(
-    RowBuffers rb, int tile_rows, int k, int pow2_k, int64_t out_batch_stride, int64_t out_row0,
-    int32_t* __restrict__ out_idx, float* __restrict__ out_score) {
-    extern __shared__ key64_t s_keep[];  // [pow2_k] kept keys, then [kStageKeys] staging
-    __shared__ SelectShared sh;
-    __shared__ key64_t s_min;
-    const int tid = threadIdx.x;
-    const int64_t row = static_cast<int64_t>(blockIdx.y) * tile_rows + blockIdx.x;
+    RowBuffers rb, int rows, int tile_rows, int k, int pow2_k, int64_t out_batch_stride,
+    int64_t out_row0, int32_t* __restrict__ out_idx, float* __restrict__ out_score) {
+    extern __shared__ key64_t s_sort_all[];  // [kRowWaves][pow2_k]
+    __shared__ int s_hist[kRowWaves][256];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * kRowWaves + wave;
+    if (r >= rows) return;
+    const int64_t row = static_cast<int64_t>(blockIdx.y) * tile_rows + r;
     const key64_t* buf = rb.keys + row * rb.cap;
-    int c = rb.count[row];
-    if (c > k) {
-        keep_top_k(buf, c, k, s_keep, s_keep + pow2_k, sh, &s_min);
-        c = k;
+    key64_t* s_sort = s_sort_all + static_cast<size_t>(wave) * pow2_k;
+    const int n = rb.count[row];
+    int c = min(n, k);
+    if (n <= 64 * kFinalizeRegKeys) {
+        RegKeys<kFinalizeRegKeys> keys;
+        keys.load(buf, n);
+        key64_t thr = 0ull;
+        int kept = 0;
+        if (n > k) thr = wave_radix_kth(keys, k, k, s_hist[wave], &kept);  // limit k: exact
+        wave_keep(keys, thr, s_sort, pow2_k);
     } else {
-        for (int i = tid; i < c; i += kTopkThreads) s_keep[i] = buf[i];
+        const StreamKeys keys{buf, n};
+        key64_t thr = 0ull;
+        int kept = 0;
+        if (n > k) thr = wave_radix_kth(keys, k, k, s_hist[wave], &kept);
+        wave_keep(keys, thr, s_sort, pow2_k);
     }
     int P = 1;
     while (P < c) P <<= 1;
-    for (int i = c + tid; i < P; i += kTopkThreads) s_keep[i] = 0ull;
-    __syncthreads();
+    for (int i = c + lane; i < P; i += 64) s_sort[i] = 0ull;
+    __builtin_amdgcn_wave_barrier();
     // bitonic sort, best (largest key) first
     for (int size = 2; size <= P; size <<= 1) {
         for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            for (int i = tid; i < (P >> 1); i += kTopkThreads) {
+            for (int i = lane; i < (P >> 1); i += 64) {
                 const int lo = 2 * i - (i & (stride - 1));
                 const int hi = lo + stride;
                 const bool descending = (lo & size) == 0;
-                const key64_t x = s_keep[lo], y = s_keep[hi];
+                const key64_t x = s_sort[lo], y = s_sort[hi];
                 if ((x < y) == descending) {
-                    s_keep[lo] = y;
-                    s_keep[hi] = x;
+                    s_sort[lo] = y;
+                    s_sort[hi] = x;
                 }
             }
-            __syncthreads();
+            __builtin_amdgcn_wave_barrier();
         }
     }
-    const int64_t o = (static_cast<int64_t>(blockIdx.y) * out_batch_stride + out_row0 + blockIdx.x) * k;
-    for (int j = tid; j < k; j += kTopkThreads) {
+    const int64_t o = (static_cast<int64_t>(blockIdx.y) * out_batch_stride + out_row0 + r) * k;
+    for (int j = lane; j < k; j += 64) {
         if (j < c) {
-            const key64_t key = s_keep[j];
+            const key64_t key = s_sort[j];
             out_idx[o + j] = key_index(key);
             out_score[o + j] = key_score(key);
         } else {  // Section 4.2: pad
@@ -262,11 +320,8 @@ hipError_t launch_filter_scores(const float* scores, int32_t R, int32_t n_cols, 
 
 hipError_t launch_compact(const RowBuffers& rb, int32_t B, int32_t rows, int32_t tile_rows, int32_t k,
                           int32_t trigger, hipStream_t stream) {
-    const size_t lds = (static_cast<size_t>(k) + kStageKeys) * sizeof(key64_t);
-    hipError_t e = allow_lds(reinterpret_cast<const void*>(compact_kernel), lds);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(compact_kernel, dim3(rows, B), dim3(kTopkThreads), lds, stream, rb, rows, tile_rows,
-                       k, trigger);
+    hipLaunchKernelGGL(compact_kernel, dim3((rows + kRowWaves - 1) / kRowWaves, B), dim3(kTopkThreads), 0, stream, rb, rows, tile_rows, k,
+                       trigger);
     return hipGetLastError();
 }
 
@@ -275,11 +330,11 @@ hipError_t launch_finalize(const RowBuffers& rb, int32_t B, int32_t rows, int32_
                            float* out_score, hipStream_t stream) {
     int pow2_k = 1;
     while (pow2_k < k) pow2_k <<= 1;
-    const size_t lds = (static_cast<size_t>(pow2_k) + kStageKeys) * sizeof(key64_t);
+    const size_t lds = static_cast<size_t>(kRowWaves) * pow2_k * sizeof(key64_t);
     hipError_t e = allow_lds(reinterpret_cast<const void*>(finalize_kernel), lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(finalize_kernel, dim3(rows, B), dim3(kTopkThreads), lds, stream, rb, tile_rows, k,
-                       pow2_k, out_batch_stride, out_row0, out_idx, out_score);
+    hipLaunchKernelGGL(finalize_kernel, dim3((rows + kRowWaves - 1) / kRowWaves, B), dim3(kTopkThreads), lds,
+                       stream, rb, rows, tile_rows, k, pow2_k, out_batch_stride, out_row0, out_idx, out_score);
     return hipGetLastError();
 }
 
