@@ -66,11 +66,11 @@ typedef struct {
     size_t workspace_bytes;  /* what si_workspace_bytes returns for (c_S, c_T)                */
 } si_plan;
 
-/* Chunk-size rule of Section 6.5 restated for this chip: pick (c_S, c_T) whose workspace
- * fits `hbm_budget_bytes`.  c_T is taken so that one key tile stays resident in an XCD's L2
- * and c_S as large as the budget allows up to the point where the launch fills the chip a
- * few times over.  Host only, no GPU call.  Fails with SI_ERR_WORKSPACE_TOO_SMALL when not
- * even the smallest tiling fits. */
+/* Chunk-size rule of Section 6.5 ("key tile as large as fits, then the query tile") as measured
+ * on this chip: larger tiles win on both axes, so the plan is the largest key tile (up to 32768)
+ * for which a query tile at least as long (up to 32768 rows over the batch) still fits
+ * `hbm_budget_bytes`; for tiny budgets the query tile shrinks to 8 and the key tile follows.
+ * Host only, no GPU call.  Fails with SI_ERR_WORKSPACE_TOO_SMALL when nothing fits. */
 si_status si_plan_tiles(const si_dims* dims, int32_t m, int32_t k, si_mask_mode mask_mode,
                         size_t hbm_budget_bytes, si_plan* out);
 

@@ -145,26 +145,46 @@ si_status si_plan_tiles(const si_dims* dims, int32_t m, int32_t k, si_mask_mode 
     si_status st = check_dims(dims, m, k, mask_mode);
     if (st != SI_OK) return st;
     if (!out) return SI_ERR_INVALID_ARG;
-    // Key tile: the K rows of one tile (c_T * D bf16) should stay resident in one XCD's 4 MiB
-    // L2 while every workgroup of the launch streams them: aim for 2 MiB.
-    int64_t c_T = std::min<int64_t>(dims->T, (2ll << 20) / (2ll * dims->D));
-    // Query tile: as large as the budget allows, up to 8192 rows per batch entry (1024
-    // workgroups of 8 queries: four rounds over 256 CUs), in multiples of the workgroup's 8.
-    const int64_t cap = std::min<int64_t>(dims->S, std::max<int64_t>(kQueriesPerBlock, 8192 / dims->B));
-    for (;;) {
-        int64_t c_S = cap;
-        while (c_S > kQueriesPerBlock && workspace_bytes_for(dims->B, c_S, c_T, k) > hbm_budget_bytes)
-            c_S = std::max<int64_t>(kQueriesPerBlock, (c_S / 2 + 7) / 8 * 8);
-        c_S = std::min<int64_t>(c_S, dims->S);
-        if (workspace_bytes_for(dims->B, c_S, c_T, k) <= hbm_budget_bytes) {
-            out->c_S = static_cast<int32_t>(c_S);
-            out->c_T = static_cast<int32_t>(c_T);
-            out->workspace_bytes = workspace_bytes_for(dims->B, c_S, c_T, k);
-            return SI_OK;
+    // Measured on MI355X (flash_1m, 8 GB budget): larger tiles win on both axes.  Fewer, longer
+    // launches lose less to the drain at every kernel boundary, and every key tile costs one
+    // pass of the compaction kernel over all rows.  The workgroups of a launch walk the key
+    // tile in step, so the part of K in use at any moment is small whatever c_T is.  Rule:
+    // the largest key tile (up to 32768) for which a query tile at least as long (up to 32768)
+    // still fits the budget; failing that, the smallest query tile and a shrinking key tile.
+    const int64_t B = dims->B;
+    const int64_t s_cap = std::min<int64_t>(dims->S, std::max<int64_t>(kQueriesPerBlock, 32768 / B));
+    auto fit_rows = [&](int64_t c_T) {  // longest query tile (multiple of 8, or all of S) within the budget
+        int64_t lo = 0, hi = s_cap;     // workspace grows with c_S: bisect
+        while (lo < hi) {
+            const int64_t mid = (lo + hi + 1) / 2;
+            if (workspace_bytes_for(B, mid, c_T, k) <= hbm_budget_bytes) lo = mid; else hi = mid - 1;
         }
-        if (c_T <= 32) return SI_ERR_WORKSPACE_TOO_SMALL;
-        c_T = std::max<int64_t>(32, c_T / 2);
+        if (lo < dims->S) lo = lo / kQueriesPerBlock * kQueriesPerBlock;
+        return lo;
+    };
+    static const int64_t key_tiles[] = {32768, 24576, 16384, 12288, 8192, 6144, 4096, 3072, 2048, 1024,
+                                        512, 256, 128, 64, 32};
+    int64_t best_S = 0, best_T = 0;
+    for (int64_t cand : key_tiles) {
+        const int64_t c_T = std::min<int64_t>(cand, dims->T);
+        const int64_t c_S = fit_rows(c_T);
+        if (c_S >= std::min<int64_t>(c_T, s_cap)) {  // balanced tile found
+            best_S = c_S;
+            best_T = c_T;
+            break;
+        }
+        if (c_S >= kQueriesPerBlock || c_S == dims->S) {  // remember the widest key tile that fits at all
+            if (best_S == 0 || c_S * c_T > best_S * best_T) {
+                best_S = c_S;
+                best_T = c_T;
+            }
+        }
     }
+    if (best_S == 0) return SI_ERR_WORKSPACE_TOO_SMALL;
+    out->c_S = static_cast<int32_t>(best_S);
+    out->c_T = static_cast<int32_t>(best_T);
+    out->workspace_bytes = workspace_bytes_for(B, best_S, best_T, k);
+    return SI_OK;
 }
 
 si_status si_score_tile(const void* q, const void* K, const float* w, const si_dims* dims,

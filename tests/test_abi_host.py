@@ -40,21 +40,27 @@ def test_strerror_and_sizes():
 
 
 def test_plan_respects_budget_and_shapes():
-    # 1M context under 8 GB (headline configuration)
-    c_S, c_T, ws = P.si_plan_tiles(1, 1 << 20, 64, 128, 1 << 18, 4, 1024, 1, 8 * 10**9)
-    assert ws <= 8 * 10**9 and c_T * 128 * 2 <= 2 << 20 and c_S % 8 == 0 and c_S >= 2048
-    assert ws == P.si_workspace_bytes(1, 1 << 20, 64, 128, 1 << 18, 1024, c_S, c_T)
-    # a tight budget shrinks the query tile first, then the key tile
-    c_S2, c_T2, ws2 = P.si_plan_tiles(1, 1 << 20, 64, 128, 1 << 18, 4, 1024, 1, 8 << 20)
-    assert ws2 <= 8 << 20 and c_S2 < c_S and c_S2 >= 8
-    c_S3, c_T3, ws3 = P.si_plan_tiles(1, 1 << 20, 64, 128, 1 << 18, 4, 1024, 1, 200 << 10)
-    assert ws3 <= 200 << 10 and c_S3 == 8 and c_T3 < c_T2
+    dims = (1, 1 << 20, 64, 128, 1 << 18)
+    # 1M context under 8 GB (headline configuration): large, balanced tiles
+    c_S, c_T, ws = P.si_plan_tiles(*dims, 4, 1024, 1, 8 * 10**9)
+    assert ws <= 8 * 10**9 and c_S % 8 == 0 and c_S >= c_T >= 16384
+    assert ws == P.si_workspace_bytes(*dims, 1024, c_S, c_T)
+    # the tile area never grows when the budget shrinks, and the plan always fits it
+    prev = (c_S, c_T)
+    for budget in (4 * 10**9, 10**9, 64 << 20, 8 << 20, 200 << 10):
+        s_, t_, w_ = P.si_plan_tiles(*dims, 4, 1024, 1, budget)
+        assert w_ <= budget and w_ == P.si_workspace_bytes(*dims, 1024, s_, t_)
+        assert s_ * t_ <= prev[0] * prev[1] and s_ >= 8 and s_ % 8 == 0 and t_ >= 32
+        prev = (s_, t_)
     with pytest.raises(P.StreamIndexError) as e:
-        P.si_plan_tiles(1, 1 << 20, 64, 128, 1 << 18, 4, 1024, 1, 1024)
+        P.si_plan_tiles(*dims, 4, 1024, 1, 1024)
     assert e.value.status == P.SI_ERR_WORKSPACE_TOO_SMALL
     # small problems are clamped to their own size
     c_S, c_T, _ = P.si_plan_tiles(1, 1024, 4, 32, 256, 4, 16, 0, 1 << 30)
     assert (c_S, c_T) == (1024, 256)
+    # batch entries share the budget
+    s4, t4, w4 = P.si_plan_tiles(4, 65536, 64, 128, 16384, 4, 512, 1, 8 * 10**9)
+    assert w4 <= 8 * 10**9 and s4 * 4 <= 32768 and t4 == 16384
 
 
 @pytest.mark.parametrize("bad,status", [
