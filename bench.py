@@ -52,7 +52,7 @@ def main() -> int:
 
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (queries would shard across GPUs with a "
-              "replicated key cache; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+              "replicated key cache, no exchange step); run with --gpus 1", file=sys.stderr)
         return 2
 
     import numpy as np

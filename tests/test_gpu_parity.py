@@ -249,3 +249,59 @@ def test_duplicate_keys_and_zero_weights_tie_break(oracle):
         present = [s for s in (9, 40, 41) if s in row]
         assert present == sorted(present) and present == [9, 40, 41][:len(present)]
     assert np.array_equal(got, ri)  # this small case has no near-ties besides the planted exact ones
+
+
+# ------------------------------------------------------------------ the paper's other sweeps, at V4 head shape
+@pytest.mark.parametrize("B,S,m,k,mask", [
+    (1, 2048, 4, 64, 1),      # k sweep of Section 6.5 (Table 5): 64 ... 2048
+    (1, 2048, 4, 256, 1),
+    (1, 4096, 2, 2048, 1),    # k = 2048 needs T >= 2048 to fill a row
+    (2, 1536, 4, 128, 1),     # batch 2
+    (1, 1024, 4, 512, 0),     # no mask: every query sees all T keys, k > T pads
+])
+def test_v4_head_shape_sweeps(oracle, B, S, m, k, mask):
+    H, D = 64, 128
+    T = S // m
+    q, K, w = _rand_problem(9, B, S, H, D, T)
+    qd, Kd, wd = q.to(DEV), K.to(DEV), w.to(DEV)
+    ref = None
+    for c_S, c_T in [(S, T), (520, 192)]:
+        _say(f"v4 sweep B={B} S={S} m={m} k={k} mask={mask} c_S={c_S} c_T={c_T}")
+        oi, os_ = _run_tiled(qd, Kd, wd, m, k, mask, c_S, c_T)
+        if ref is None:
+            rows = np.arange(0, B * S, 3)  # every third row keeps the CPU time small
+            stats = parity.check_rows(
+                oracle, W.bf16_bits(q).reshape(B * S, H, D)[rows], w.numpy().reshape(B * S, H)[rows],
+                W.bf16_bits(K), (rows // S).astype(np.int32), (rows % S).astype(np.int64), m, k, mask,
+                oi.cpu().numpy().reshape(B * S, k)[rows], os_.cpu().numpy().reshape(B * S, k)[rows])
+            _say(f"  {stats}")
+            assert stats["mean_recall"] > 0.9999 and stats["min_recall"] >= 1.0 - 2.0 / k
+            ref = (oi, os_)
+        else:
+            assert torch.equal(oi, ref[0]) and torch.equal(os_.view(torch.int32), ref[1].view(torch.int32))
+
+
+def test_adversarial_score_order_through_the_whole_path(oracle):
+    """Keys sorted so that every later key scores higher for every query: nothing can be filtered,
+    every tile floods the row buffers, compaction runs on its streaming path."""
+    B, S, H, D, m, k = 1, 256, 1, 32, 1, 64
+    T = 6000
+    g = torch.Generator(device="cpu").manual_seed(10)
+    base = torch.randn((D,), generator=g).abs() + 0.1
+    q = (base[None, None, None, :] * (1.0 + torch.rand((B, S, H, D), generator=g))).to(torch.bfloat16)
+    scale = torch.linspace(0.5, 4.0, T)
+    K = (base[None, None, :] * scale[None, :, None]).to(torch.bfloat16)
+    w = torch.ones((B, S, H))
+    ref = None
+    for c_S, c_T in [(S, T), (S, 4096), (64, 1000)]:
+        _say(f"adversarial c_S={c_S} c_T={c_T}")
+        oi, os_ = _run_tiled(q.to(DEV), K.to(DEV), w.to(DEV), m, k, 0, c_S, c_T)
+        if ref is None:
+            stats = parity.check_rows(
+                oracle, W.bf16_bits(q).reshape(S, H, D), w.numpy().reshape(S, H), W.bf16_bits(K),
+                np.zeros(S, dtype=np.int32), np.arange(S, dtype=np.int64), m, k, 0,
+                oi.cpu().numpy().reshape(S, k), os_.cpu().numpy().reshape(S, k))
+            assert stats["mean_recall"] > 0.999, stats
+            ref = (oi, os_)
+        else:
+            assert torch.equal(oi, ref[0]) and torch.equal(os_.view(torch.int32), ref[1].view(torch.int32))
