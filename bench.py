@@ -45,6 +45,8 @@ def main() -> int:
     ap.add_argument("--c-t", type=int, default=0, help="explicit key tile (0 = planned)")
     ap.add_argument("--oracle-rows", type=int, default=256,
                     help="rows of the workload the CPU oracle is timed (and checked) on; 0 = skip")
+    ap.add_argument("--seq-len", type=int, default=0, help="override S of the workload (T = S/m follows)")
+    ap.add_argument("--topk", type=int, default=0, help="override k of the workload")
     ap.add_argument("--calibration-mib", type=int, default=0,
                     help="also run one plain elementwise kernel reading and writing this many MiB "
                          "(a known-size reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -67,6 +69,9 @@ def main() -> int:
     dev = "cuda:0"
     torch.cuda.set_device(0)
     wl = W.CONFIGS[args.workload]
+    if args.seq_len or args.topk:  # the paper's S and k sweeps on the same head shape
+        wl = wl.scaled(S=args.seq_len or wl.S, k=args.topk or wl.k)
+        wl = wl.scaled(name=f"{args.workload}[S={wl.S},k={wl.k}]")
     T = wl.T
 
     q, K, w, info = W.make_inputs(wl, device=dev)

@@ -1,8 +1,10 @@
 // Host driver: argument checks, tile planning, workspace carve-up and the nested tile loop
-// of Algorithm 2 (outer loop over query tiles, inner loop over key tiles, running top-k
-// buffer per query, write-out after the last key tile).  Key tiles that hold no legal key for
-// any query of the query tile are not visited (Algorithm 2 visits them; their masked entries
-// can never be selected, so the result is the same).
+// of Algorithm 2 (outer loop over query tiles, inner loop over key tiles, per-query running
+// state, write-out after the last key tile).  Per key tile: one score kernel that appends the
+// surviving candidates to the row buffers, one compaction kernel; per query tile: one init and
+// one finalize kernel.  Key tiles that hold no legal key for any query of the query tile are
+// not visited (Algorithm 2 visits them; their masked entries can never be selected, so the
+// result is the same).
 
 #include <algorithm>
 #include <vector>
@@ -234,11 +236,11 @@ si_status si_indexer_topk_tiled(const void* q, const void* K, const float* w,
                                            static_cast<int32_t>(t0), rows, width, c_S, rb, hs);
             });
             if (e != hipSuccess) return hip_fail(e);
-            e = timed(kProfMerge, hs, [&] { return launch_compact(rb, d.B, rows, c_S, k, 2 * k, hs); });
+            e = timed(kProfCompact, hs, [&] { return launch_compact(rb, d.B, rows, c_S, k, 2 * k, hs); });
             if (e != hipSuccess) return hip_fail(e);
             t0 += width;
         }
-        e = timed(kProfWriteout, hs, [&] {
+        e = timed(kProfFinalize, hs, [&] {
             return launch_finalize(rb, d.B, rows, c_S, k, d.S, s0, out_idx, out_score, hs);
         });
         if (e != hipSuccess) return hip_fail(e);
@@ -273,14 +275,14 @@ si_status si_topk_from_scores(const float* scores, int32_t R, int32_t n_cols,
     if (e != hipSuccess) return hip_fail(e);
     for (int64_t t0 = 0; t0 < n_cols; t0 += c_T) {
         const int32_t width = static_cast<int32_t>(std::min<int64_t>(c_T, n_cols - t0));
-        e = timed(kProfSelect, hs, [&] {
+        e = timed(kProfFilterScores, hs, [&] {
             return launch_filter_scores(scores, R, n_cols, static_cast<int32_t>(t0), width, legal, rb, hs);
         });
         if (e != hipSuccess) return hip_fail(e);
-        e = timed(kProfMerge, hs, [&] { return launch_compact(rb, 1, R, R, k, 2 * k, hs); });
+        e = timed(kProfCompact, hs, [&] { return launch_compact(rb, 1, R, R, k, 2 * k, hs); });
         if (e != hipSuccess) return hip_fail(e);
     }
-    e = timed(kProfWriteout, hs, [&] { return launch_finalize(rb, 1, R, R, k, R, 0, out_idx, out_score, hs); });
+    e = timed(kProfFinalize, hs, [&] { return launch_finalize(rb, 1, R, R, k, R, 0, out_idx, out_score, hs); });
     return e == hipSuccess ? SI_OK : hip_fail(e);
 }
 

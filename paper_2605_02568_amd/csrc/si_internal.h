@@ -54,7 +54,7 @@ struct RowBuffers {
 };
 RowBuffers carve_workspace(void* base, int64_t rows, int64_t k, int64_t c_T);
 
-enum ProfileClass { kProfScore = 0, kProfSelect = 1, kProfMerge = 2, kProfWriteout = 3, kProfInit = 4 };
+enum ProfileClass { kProfScore = 0, kProfFilterScores = 1, kProfCompact = 2, kProfFinalize = 3, kProfInit = 4 };
 
 // Kernel launchers (each enqueues exactly one kernel on `stream`).
 // Dense fp32 tile [B, tile_rows, tile_cols] of queries [s0, s0+rows) x keys [t0, t0+width).
