@@ -188,7 +188,7 @@ __global__ __launch_bounds__(kTopkThreads) void filter_scores_kernel(
 }
 
 
-__host__ __device__ inline int compact_limit(int k) { return k + k / 4; }
+__host__ __device__ inline int compact_limit(int k) { return k + k / 16; }
 constexpr int kCompactRegKeys = 48;   // compaction keeps rows of up to 3072 keys in registers
 constexpr int kFinalizeRegKeys = 32;  // finalize: rows of up to 2048 keys
 

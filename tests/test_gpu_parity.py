@@ -305,3 +305,23 @@ def test_adversarial_score_order_through_the_whole_path(oracle):
             ref = (oi, os_)
         else:
             assert torch.equal(oi, ref[0]) and torch.equal(os_.view(torch.int32), ref[1].view(torch.int32))
+
+
+def test_profile_counters_follow_the_launches():
+    """Per-kernel timing facility: one score launch and one compaction per key tile, one init and
+    one finalize per query tile; durations are positive; disabled means nothing is recorded."""
+    B, S, H, D, m, k = 1, 512, 64, 128, 1, 32
+    T = 4096
+    q, K, w = _rand_problem(11, B, S, H, D, T)
+    qd, Kd, wd = q.to(DEV), K.to(DEV), w.to(DEV)
+    P.si_profile_reset()
+    P.si_profile_enable(True)
+    _run_tiled(qd, Kd, wd, m, k, 0, 256, 2048)  # 2 query tiles; key tiles 1024, 1024, 2048
+    prof = P.si_profile_read()
+    P.si_profile_enable(False)
+    assert prof["score_tile"][1] == 2 * 3 and prof["compact"][1] == 2 * 3
+    assert prof["init"][1] == 2 and prof["finalize"][1] == 2 and prof["filter_scores"][1] == 0
+    assert all(ms > 0 for name, (ms, n) in prof.items() if n > 0)
+    P.si_profile_reset()
+    _run_tiled(qd, Kd, wd, m, k, 0, 256, 2048)
+    assert all(n == 0 for _, n in P.si_profile_read().values())
