@@ -52,7 +52,7 @@ void score_tile_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ 
                        int s0, int t0, int rows, int width, int tile_rows, int tile_cols,
                        float* __restrict__ tile, RowBuffers rb) {
     constexpr int KS = D / 16;             // MFMA steps along d
-    constexpr int EPG = 16 * HB / KS;      // epilogue elements handled next to one MFMA step
+    constexpr int EPM = 16 / KS;           // epilogue elements handled next to one MFMA
     static_assert(16 * HB % KS == 0, "epilogue elements must split evenly over the MFMA steps");
     // LDS key rows are unpadded (2*D bytes); the 16-byte pieces of a row are XOR-swizzled so
     // that the 16 lanes served together by one ds_read_b128 hit 16 different bank groups:
@@ -159,8 +159,10 @@ void score_tile_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ 
     // Software pipeline, one step per 32-key sub-block: the MFMAs of sub-block g fill one
     // accumulator set while the ReLU / weight / head-sum epilogue drains the other one (sub-block
     // g-1), and the key operand of sub-block g+1 is read from LDS into the registers the MFMAs
-    // have just consumed.  The scheduling barriers pin this interleaving: per MFMA step, HB MFMAs,
-    // EPG epilogue elements, one LDS read.
+    // have just consumed.  The scheduling barriers pin this interleaving: per MFMA, 16/KS epilogue
+    // elements and (in the last head block) one LDS read.  Each head block's KS MFMAs are issued
+    // back to back as one dependent accumulator chain, which measured slightly faster than
+    // alternating the head blocks.
     floatx16 accA[HB], accB[HB];
     const floatx16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
@@ -168,15 +170,15 @@ void score_tile_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ 
 #define SI_STEP(CUR, PREV, OUT, NEXT_BYTEOFF)                                                      \
     {                                                                                               \
         float s_ = 0.0f;                                                                            \
-        _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                         \
-            _Pragma("unroll") for (int hb = 0; hb < HB; ++hb)                                       \
+        _Pragma("unroll") for (int hb = 0; hb < HB; ++hb)                                           \
+            _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                     \
                 CUR[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[hb][ks], bq[ks],                \
                                                                   ks == 0 ? zero16 : CUR[hb], 0, 0, 0); \
-            _Pragma("unroll") for (int e = ks * EPG; e < (ks + 1) * EPG; ++e)                       \
-                s_ = fmaf(wr[e / 16][e % 16], relu(PREV[e / 16][e % 16]), s_);                      \
-            bq[ks] = SI_KREAD(NEXT_BYTEOFF, ks);                                                    \
-            __builtin_amdgcn_sched_barrier(0);                                                      \
-        }                                                                                           \
+                _Pragma("unroll") for (int e = (hb * KS + ks) * EPM; e < (hb * KS + ks + 1) * EPM; ++e)   \
+                    s_ = fmaf(wr[e / 16][e % 16], relu(PREV[e / 16][e % 16]), s_);                  \
+                if (hb == HB - 1) bq[ks] = SI_KREAD(NEXT_BYTEOFF, ks);                              \
+                __builtin_amdgcn_sched_barrier(0);                                                  \
+            }                                                                                       \
         OUT = s_ + __shfl_xor(s_, 32);                                                              \
     }
     // 64 finished scores (lane l holds key KEY0 + l): append the kept ones / store the tile row.

@@ -15,7 +15,8 @@
 //             MSB-first radix descent over the 64-bit keys (8 bits per pass, LDS histogram),
 //             and the threshold is raised.  Tiles narrower than k simply accumulate until
 //             then (the "saturated tile" case of Section 6.6 keeps every entry).
-//   finalize: last cut to k, bitonic sort in LDS, decode to (index, score), pad (Section 4.2).
+//   finalize: last cut to k, bitonic sort (LDS + registers), decode to (index, score), pad
+//             (Section 4.2).
 
 #include "si_internal.h"
 
@@ -144,21 +145,137 @@ __device__ inline key64_t wave_radix_kth(const Keys& keys, int k, int limit, int
     return prefix;
 }
 
-// Writes the row's keys >= thr to dst[0, ...) in key order (dst may be the row buffer itself:
-// a block of keys is always read before anything at or behind it is written).  `cap` bounds
-// the writes.  Returns how many were written.
-template <typename Keys>
-__device__ inline int wave_keep(const Keys& keys, key64_t thr, key64_t* dst, int cap) {
+struct IdentitySlot {
+    __device__ inline int operator()(int i) const { return i; }
+};
+
+// Writes the row's keys >= thr to dst[slot(0)], dst[slot(1)], ... in key order (dst may be the
+// row buffer itself when slot is the identity: a block of keys is always read before anything
+// at or behind it is written).  `cap` bounds the logical positions written.  Returns how many
+// keys qualified.
+template <typename Keys, typename Slot = IdentitySlot>
+__device__ inline int wave_keep(const Keys& keys, key64_t thr, key64_t* dst, int cap, Slot slot = Slot()) {
     int pos = 0;
     keys.sweep([&](key64_t key, bool valid) {
         const bool keep = valid && key >= thr;
         const unsigned long long mask = __ballot(keep);
         const int below = __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(mask >> 32),
                           __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(mask), 0u));
-        if (keep && pos + below < cap) dst[pos + below] = key;
+        if (keep && pos + below < cap) dst[slot(pos + below)] = key;
         pos += __popcll(mask);
     });
     return pos;
+}
+
+// ---- wave-level sort ------------------------------------------------------------------------
+// Bitonic network over P keys (a power of two >= 16) in one wave's slice of LDS, best (largest)
+// key first.  A compare-exchange at stride 2^j only pairs keys whose positions differ in bit j,
+// so a lane that holds the 2^NB keys spanning bits [b, b+NB) of the position can run NB
+// consecutive strides of the network in registers: one LDS round trip per group of up to four
+// strides instead of one per stride (15 instead of 55 for P = 1024).
+// Sixteen keys (128 B) are followed by two slots of padding, so that lanes reading their own
+// 16-key block with 128-bit loads start in different banks.
+struct SortSlot {
+    __device__ inline int operator()(int i) const { return i + ((i >> 4) << 1); }
+};
+__host__ __device__ inline int sort_slots(int P) { return P + P / 8; }
+
+__device__ inline void compare_exchange(key64_t& x, key64_t& y, bool descending) {
+    const bool swap = (x < y) == descending;
+    const key64_t a = swap ? y : x;
+    const key64_t b = swap ? x : y;
+    x = a;
+    y = b;
+}
+
+// Strides 2^(b+NB-1) .. 2^b of the merge phase that builds sorted runs of `size` (> 2^(b+NB-1)).
+template <int NB>
+__device__ inline void sort_pass(key64_t* s, int P, int b, int size) {
+    constexpr int E = 1 << NB;
+    const SortSlot slot;
+    const int lane = threadIdx.x & 63;
+    for (int u = lane; u < (P >> NB); u += 64) {
+        const int base = (u & ((1 << b) - 1)) | ((u >> b) << (b + NB));
+        const bool descending = (base & size) == 0;
+        key64_t v[E];
+#pragma unroll
+        for (int j = 0; j < E; ++j) v[j] = s[slot(base | (j << b))];
+#pragma unroll
+        for (int d = E >> 1; d > 0; d >>= 1)
+#pragma unroll
+            for (int i = 0; i < (E >> 1); ++i) {
+                const int lo = 2 * i - (i & (d - 1));
+                compare_exchange(v[lo], v[lo + d], descending);
+            }
+#pragma unroll
+        for (int j = 0; j < E; ++j) s[slot(base | (j << b))] = v[j];
+    }
+    __builtin_amdgcn_wave_barrier();
+}
+
+// The four lowest strides (8, 4, 2, 1) on a lane's own block of 16 consecutive keys; with
+// FIRST, the whole network up to runs of 16 (sizes 2, 4, 8, 16) instead.
+template <bool FIRST>
+__device__ inline void sort_block16(key64_t* s, int P, int size) {
+    typedef key64_t key64x2 __attribute__((ext_vector_type(2)));
+    const SortSlot slot;
+    const int lane = threadIdx.x & 63;
+    for (int base = 16 * lane; base < P; base += 16 * 64) {
+        key64x2* blk = reinterpret_cast<key64x2*>(s + slot(base));  // 16-byte aligned
+        key64_t v[16];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const key64x2 t = blk[j];
+            v[2 * j] = t.x;
+            v[2 * j + 1] = t.y;
+        }
+        if (FIRST) {
+#pragma unroll
+            for (int sz = 2; sz <= 16; sz <<= 1)
+#pragma unroll
+                for (int d = sz >> 1; d > 0; d >>= 1)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const int lo = 2 * i - (i & (d - 1));
+                        compare_exchange(v[lo], v[lo + d], ((base + lo) & sz) == 0);
+                    }
+        } else {
+            const bool descending = (base & size) == 0;
+#pragma unroll
+            for (int d = 8; d > 0; d >>= 1)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int lo = 2 * i - (i & (d - 1));
+                    compare_exchange(v[lo], v[lo + d], descending);
+                }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            key64x2 t;
+            t.x = v[2 * j];
+            t.y = v[2 * j + 1];
+            blk[j] = t;
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+}
+
+// s: sort_slots(P) keys of LDS owned by this wave, key i at s[SortSlot()(i)].
+__device__ inline void wave_sort_descending(key64_t* s, int P) {
+    sort_block16<true>(s, P, 0);
+    for (int lg = 5; (1 << lg) <= P; ++lg) {
+        const int size = 1 << lg;
+        for (int top = lg; top > 4;) {  // stride bits [4, lg), four at a time from the top
+            const int nb = min(4, top - 4);
+            const int b = top - nb;
+            if (nb == 4) sort_pass<4>(s, P, b, size);
+            else if (nb == 3) sort_pass<3>(s, P, b, size);
+            else if (nb == 2) sort_pass<2>(s, P, b, size);
+            else sort_pass<1>(s, P, b, size);
+            top = b;
+        }
+        sort_block16<false>(s, P, size);
+    }
 }
 
 // Dense-score front end (entry point si_topk_from_scores): appends the legal entries of one
@@ -194,7 +311,7 @@ constexpr int kFinalizeRegKeys = 32;  // finalize: rows of up to 2048 keys
 
 // Merge step, done lazily: a row's buffer holds the k best keys of an earlier prefix plus
 // everything appended since.  Once it holds at least `trigger` keys it is cut back to its best
-// k .. 1.25k keys (an exact cut is only needed at the very end) and the row's threshold is
+// k .. k + k/16 keys (an exact cut is only needed at the very end) and the row's threshold is
 // raised to the score below which everything was dropped.  One wave per row.
 __global__ __launch_bounds__(kTopkThreads) void compact_kernel(RowBuffers rb, int rows, int tile_rows,
                                                                int k, int trigger) {
@@ -227,11 +344,11 @@ __global__ __launch_bounds__(kTopkThreads) void compact_kernel(RowBuffers rb, in
 }
 
 // After the last key tile: final exact cut to k, sort best first, decode, pad (Section 4.2).
-// One wave per row; the sort is a bitonic network over the wave's own slice of LDS.
+// One wave per row; the sort runs in the wave's own slice of LDS.
 __global__ __launch_bounds__(kTopkThreads) void finalize_kernel(
     RowBuffers rb, int rows, int tile_rows, int k, int pow2_k, int64_t out_batch_stride,
     int64_t out_row0, int32_t* __restrict__ out_idx, float* __restrict__ out_score) {
-    extern __shared__ key64_t s_sort_all[];  // [kRowWaves][pow2_k]
+    extern __shared__ __attribute__((aligned(16))) key64_t s_sort_all[];  // [kRowWaves][sort_slots(pow2_k)]
     __shared__ int s_hist[kRowWaves][256];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
@@ -239,7 +356,8 @@ __global__ __launch_bounds__(kTopkThreads) void finalize_kernel(
     if (r >= rows) return;
     const int64_t row = static_cast<int64_t>(blockIdx.y) * tile_rows + r;
     const key64_t* buf = rb.keys + row * rb.cap;
-    key64_t* s_sort = s_sort_all + static_cast<size_t>(wave) * pow2_k;
+    key64_t* s_sort = s_sort_all + static_cast<size_t>(wave) * sort_slots(pow2_k);
+    const SortSlot slot;
     const int n = rb.count[row];
     int c = min(n, k);
     if (n <= 64 * kFinalizeRegKeys) {
@@ -248,38 +366,23 @@ __global__ __launch_bounds__(kTopkThreads) void finalize_kernel(
         key64_t thr = 0ull;
         int kept = 0;
         if (n > k) thr = wave_radix_kth(keys, k, k, s_hist[wave], &kept);  // limit k: exact
-        wave_keep(keys, thr, s_sort, pow2_k);
+        wave_keep(keys, thr, s_sort, pow2_k, slot);
     } else {
         const StreamKeys keys{buf, n};
         key64_t thr = 0ull;
         int kept = 0;
         if (n > k) thr = wave_radix_kth(keys, k, k, s_hist[wave], &kept);
-        wave_keep(keys, thr, s_sort, pow2_k);
+        wave_keep(keys, thr, s_sort, pow2_k, slot);
     }
-    int P = 1;
+    int P = 16;
     while (P < c) P <<= 1;
-    for (int i = c + lane; i < P; i += 64) s_sort[i] = 0ull;
+    for (int i = c + lane; i < P; i += 64) s_sort[slot(i)] = 0ull;  // empty keys sort last
     __builtin_amdgcn_wave_barrier();
-    // bitonic sort, best (largest key) first
-    for (int size = 2; size <= P; size <<= 1) {
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            for (int i = lane; i < (P >> 1); i += 64) {
-                const int lo = 2 * i - (i & (stride - 1));
-                const int hi = lo + stride;
-                const bool descending = (lo & size) == 0;
-                const key64_t x = s_sort[lo], y = s_sort[hi];
-                if ((x < y) == descending) {
-                    s_sort[lo] = y;
-                    s_sort[hi] = x;
-                }
-            }
-            __builtin_amdgcn_wave_barrier();
-        }
-    }
+    wave_sort_descending(s_sort, P);
     const int64_t o = (static_cast<int64_t>(blockIdx.y) * out_batch_stride + out_row0 + r) * k;
     for (int j = lane; j < k; j += 64) {
         if (j < c) {
-            const key64_t key = s_sort[j];
+            const key64_t key = s_sort[slot(j)];
             out_idx[o + j] = key_index(key);
             out_score[o + j] = key_score(key);
         } else {  // Section 4.2: pad
@@ -328,9 +431,9 @@ hipError_t launch_compact(const RowBuffers& rb, int32_t B, int32_t rows, int32_t
 hipError_t launch_finalize(const RowBuffers& rb, int32_t B, int32_t rows, int32_t tile_rows, int32_t k,
                            int64_t out_batch_stride, int64_t out_row0, int32_t* out_idx,
                            float* out_score, hipStream_t stream) {
-    int pow2_k = 1;
+    int pow2_k = 16;
     while (pow2_k < k) pow2_k <<= 1;
-    const size_t lds = static_cast<size_t>(kRowWaves) * pow2_k * sizeof(key64_t);
+    const size_t lds = static_cast<size_t>(kRowWaves) * sort_slots(pow2_k) * sizeof(key64_t);
     hipError_t e = allow_lds(reinterpret_cast<const void*>(finalize_kernel), lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(finalize_kernel, dim3((rows + kRowWaves - 1) / kRowWaves, B), dim3(kTopkThreads), lds,
