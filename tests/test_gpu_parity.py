@@ -232,6 +232,46 @@ def test_odd_shapes_all_rows(oracle, B, S, H, D, m, k, mask):
             assert torch.equal(oi, ref[0]) and torch.equal(os_.view(torch.int32), ref[1].view(torch.int32))
 
 
+def _random_shapes(n, seed):
+    """Seeded shapes that mix every supported head dimension, ragged sizes, T != S/m, k above
+    and below the number of legal keys, and tilings that cut rows and key chunks anywhere."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        B = int(rng.integers(1, 4))
+        S = int(rng.integers(1, 260))
+        H = int(rng.choice([1, 3, 8, 31, 32, 33, 48, 64]))
+        D = int(rng.choice([32, 64, 128]))
+        m = int(rng.choice([1, 2, 4, 7]))
+        mask = int(rng.integers(0, 2))
+        T = int(rng.integers(1, 600))           # explicit T: not tied to S/m
+        k = int(rng.choice([1, 2, 7, 32, 100, 257, 1024]))
+        c_S = int(rng.integers(1, S + 8))
+        c_T = int(rng.integers(1, T + 40))
+        cases.append((B, S, H, D, T, m, k, mask, c_S, c_T))
+    return cases
+
+
+@pytest.mark.parametrize("B,S,H,D,T,m,k,mask,c_S,c_T", _random_shapes(16, 20260513))
+def test_random_shapes_all_rows(oracle, B, S, H, D, T, m, k, mask, c_S, c_T):
+    q, K, w = _rand_problem(B * 1000 + S, B, S, H, D, T)
+    _say(f"random B={B} S={S} H={H} D={D} T={T} m={m} k={k} mask={mask} c_S={c_S} c_T={c_T}")
+    oi, os_ = _run_tiled(q.to(DEV), K.to(DEV), w.to(DEV), m, k, mask, c_S, c_T)
+    stats = parity.check_rows(
+        oracle, W.bf16_bits(q).reshape(B * S, H, D), w.numpy().reshape(B * S, H),
+        W.bf16_bits(K), np.repeat(np.arange(B, dtype=np.int32), S),
+        np.tile(np.arange(S, dtype=np.int64), B), m, k, mask,
+        oi.cpu().numpy().reshape(B * S, k), os_.cpu().numpy().reshape(B * S, k))
+    assert stats["min_recall"] == 1.0, stats
+    # the planned tiling (whatever fits a small budget) must give the same bits
+    ws = _workspace(P.si_workspace_bytes(B, S, H, D, T, k, S, T))
+    oi2 = torch.empty_like(oi)
+    os2 = torch.empty_like(os_)
+    P.si_indexer_topk(q.to(DEV), K.to(DEV), w.to(DEV), m, k, mask, oi2, os2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(oi, oi2) and torch.equal(os_.view(torch.int32), os2.view(torch.int32))
+
+
 def test_duplicate_keys_and_zero_weights_tie_break(oracle):
     B, S, H, D, m, k = 1, 64, 8, 32, 1, 12
     T = 64
