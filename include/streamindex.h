@@ -24,6 +24,9 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
  *     enqueued on it; the call returns without synchronising.  Results are valid once the
  *     caller has synchronised the stream.  `workspace` contents are undefined afterwards.
+ *     Only kernel launches are enqueued (no memset or copy nodes, no host synchronisation), so
+ *     a call may be recorded into a HIP graph by stream capture and replayed, provided the
+ *     profiler below is off and the pointers stay valid.
  *   - Argument errors are detected on the host before anything is launched and reported as
  *     a negative si_status; no exception crosses the boundary.
  *   - Calls that share a workspace must not overlap in time.

@@ -18,6 +18,8 @@
 //   finalize: last cut to k, bitonic sort (LDS + registers), decode to (index, score), pad
 //             (Section 4.2).
 
+#include <atomic>
+
 #include "si_internal.h"
 
 namespace si {
@@ -401,10 +403,24 @@ __global__ void init_rows_kernel(int32_t* count, float* theta, int n) {
 }
 
 namespace {
-hipError_t allow_lds(const void* fn, size_t bytes) {
+// Large k: raises finalize_kernel's dynamic LDS limit (gfx950 has 160 KB per CU).  Done once per
+// device and size, so that later calls (possibly under stream capture) launch only.
+hipError_t allow_finalize_lds(size_t bytes) {
     if (bytes <= 32 * 1024) return hipSuccess;
-    // large k: raise the kernel's dynamic LDS limit (gfx950 has 160 KB per CU)
-    return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
+    const void* fn = reinterpret_cast<const void*>(finalize_kernel);
+    constexpr int kMaxDevices = 64;
+    static std::atomic<size_t> allowed[kMaxDevices];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const bool tracked = dev >= 0 && dev < kMaxDevices;
+    if (tracked && allowed[dev].load(std::memory_order_acquire) >= bytes) return hipSuccess;
+    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
+    if (e == hipSuccess && tracked) {
+        size_t seen = allowed[dev].load(std::memory_order_relaxed);
+        while (seen < bytes && !allowed[dev].compare_exchange_weak(seen, bytes, std::memory_order_release)) {}
+    }
+    return e;
 }
 }  // namespace
 
@@ -434,7 +450,7 @@ hipError_t launch_finalize(const RowBuffers& rb, int32_t B, int32_t rows, int32_
     int pow2_k = 16;
     while (pow2_k < k) pow2_k <<= 1;
     const size_t lds = static_cast<size_t>(kRowWaves) * sort_slots(pow2_k) * sizeof(key64_t);
-    hipError_t e = allow_lds(reinterpret_cast<const void*>(finalize_kernel), lds);
+    hipError_t e = allow_finalize_lds(lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(finalize_kernel, dim3((rows + kRowWaves - 1) / kRowWaves, B), dim3(kTopkThreads), lds,
                        stream, rb, rows, tile_rows, k, pow2_k, out_batch_stride, out_row0, out_idx, out_score);
