@@ -41,6 +41,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="flash_1m")
     ap.add_argument("--budget-gb", type=float, default=8.0, help="HBM budget for the workspace")
+    ap.add_argument("--schedule", choices=["fused", "tiled"], default="tiled",
+                    help="fused: single-pass kernel (k <= 1024); tiled: one launch per (c_S x c_T) tile")
     ap.add_argument("--c-s", type=int, default=0, help="explicit query tile (0 = planned)")
     ap.add_argument("--c-t", type=int, default=0, help="explicit key tile (0 = planned)")
     ap.add_argument("--oracle-rows", type=int, default=256,
@@ -76,7 +78,11 @@ def main() -> int:
 
     q, K, w, info = W.make_inputs(wl, device=dev)
     budget = int(args.budget_gb * 1e9)
-    if args.c_s and args.c_t:
+    fused = args.schedule == "fused"
+    if fused:
+        c_S, c_T = (min(args.c_s, wl.S) if args.c_s else wl.S), 0
+        ws_bytes = P.si_fused_workspace_bytes(wl.B, wl.S, wl.H, wl.D, T, wl.k, c_S)
+    elif args.c_s and args.c_t:
         c_S, c_T = min(args.c_s, wl.S), min(args.c_t, T)
         ws_bytes = P.si_workspace_bytes(wl.B, wl.S, wl.H, wl.D, T, wl.k, c_S, c_T)
     else:
@@ -91,8 +97,12 @@ def main() -> int:
     stream = torch.cuda.current_stream()
 
     def step():
-        P.si_indexer_topk_tiled(q, K, w, wl.m, wl.k, wl.mask_mode, c_S, c_T, out_idx, out_score, ws,
-                                stream=stream)
+        if fused:
+            P.si_indexer_topk_fused(q, K, w, wl.m, wl.k, wl.mask_mode, c_S, out_idx, out_score, ws,
+                                    stream=stream)
+        else:
+            P.si_indexer_topk_tiled(q, K, w, wl.m, wl.k, wl.mask_mode, c_S, c_T, out_idx, out_score, ws,
+                                    stream=stream)
 
     for _ in range(args.warmup):
         step()
@@ -125,7 +135,7 @@ def main() -> int:
     flop_per_step = legal_pairs * wl.flop_per_pair()
     tflops = flop_per_step / sec_per_step / 1e12
 
-    score_ms, score_launches = prof["score_tile"]
+    score_ms, score_launches = prof["fused" if fused else "score_tile"]
     score_ms_per_launch = score_ms / max(1, score_launches)
     flop_per_launch = flop_per_step * args.steps / max(1, score_launches)
     achieved = flop_per_launch / (score_ms_per_launch * 1e-3) / 1e12 if score_ms > 0 else 0.0
@@ -145,7 +155,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {
             "workload": wl.name, "B": wl.B, "S": wl.S, "H_I": wl.H, "D": wl.D, "T": T, "m": wl.m,
-            "k": wl.k, "mask": "causal_block" if wl.mask_mode else "none", "c_S": c_S, "c_T": c_T,
+            "k": wl.k, "mask": "causal_block" if wl.mask_mode else "none", "schedule": args.schedule,
+            "c_S": c_S, "c_T": c_T,
             "seed": wl.seed, "sigma_w": info["sigma_w"],
         },
         "full_pairs_per_s": full_pairs / sec_per_step,
@@ -161,7 +172,7 @@ def main() -> int:
         "kernel_launches_per_step": {name: n // args.steps for name, (_, n) in prof.items()},
         "roofline": {
             "bound": "mfma",
-            "kernel": "score_tile_kernel",
+            "kernel": "indexer_fused_kernel" if fused else "score_tile_kernel",
             "achieved": achieved,
             "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s",

@@ -100,6 +100,19 @@ si_status si_indexer_topk_tiled(const void* q, const void* K, const float* w,
                                 int32_t* out_idx, float* out_score, void* workspace,
                                 size_t workspace_bytes, void* stream);
 
+/* The same result by the single-pass schedule: every group of 8 consecutive queries is taken
+ * through its whole legal key range by one resident workgroup, which filters, merges (a row is
+ * cut back to its best k whenever it has collected 2k candidates) and writes out without
+ * leaving the kernel.  No (c_S x c_T) candidate lists exist: the workspace holds one short row
+ * buffer per resident wave plus one counter per launch, independent of S and T
+ * (si_fused_workspace_bytes, about 40 MB at k = 1024).  Requires k <= 1024.
+ * c_S = queries per kernel launch (<= 0 or > S: all of them in one launch). */
+size_t si_fused_workspace_bytes(const si_dims* dims, int32_t k, int32_t c_S);
+si_status si_indexer_topk_fused(const void* q, const void* K, const float* w, const si_dims* dims,
+                                int32_t m, int32_t k, si_mask_mode mask_mode, int32_t c_S,
+                                int32_t* out_idx, float* out_score, void* workspace,
+                                size_t workspace_bytes, void* stream);
+
 /* Step "score tile" alone (the fused score kernel of Section 5): fp32 scores of queries
  * [s0, s0+c_S) against keys [t0, t0+c_T) of every batch, ReLU and the weighted head sum
  * done in registers.  tile: device [B, c_S, c_T] f32, row stride c_T.  Entries whose query
@@ -130,8 +143,9 @@ uint64_t si_materialize_bytes(const si_dims* dims);
  * those events and returns, per kernel class, the summed duration in milliseconds and the
  * number of launches since the last reset.  Classes: 0 score tile (with its fused filter),
  * 1 filter of caller-supplied scores, 2 compaction (select + merge), 3 final sort + write-out,
- * 4 buffer init.  Not thread safe; meant for a single benchmarking thread. */
-#define SI_PROFILE_CLASSES 5
+ * 4 buffer / counter init, 5 single-pass kernel.  Not thread safe; meant for a single
+ * benchmarking thread. */
+#define SI_PROFILE_CLASSES 6
 si_status si_profile_enable(int32_t on);
 si_status si_profile_reset(void);
 si_status si_profile_read(double* ms_per_class, int64_t* launches_per_class);

@@ -19,11 +19,12 @@ SI_ERR_WORKSPACE_TOO_SMALL = -3
 SI_ERR_HIP = -4
 SI_MASK_NONE = 0
 SI_MASK_CAUSAL_BLOCK = 1
-SI_PROFILE_CLASSES = 5
-PROFILE_CLASS_NAMES = ("score_tile", "filter_scores", "compact", "finalize", "init")
+SI_PROFILE_CLASSES = 6
+PROFILE_CLASS_NAMES = ("score_tile", "filter_scores", "compact", "finalize", "init", "fused")
 
 EXPORTS = (
     "si_plan_tiles", "si_workspace_bytes", "si_indexer_topk", "si_indexer_topk_tiled",
+    "si_fused_workspace_bytes", "si_indexer_topk_fused",
     "si_score_tile", "si_topk_from_scores", "si_materialize_bytes", "si_profile_enable",
     "si_profile_reset", "si_profile_read", "si_strerror", "si_last_hip_error", "si_version",
 )
@@ -67,6 +68,12 @@ def load():
     L.si_indexer_topk_tiled.argtypes = [c_void_p, c_void_p, c_void_p, POINTER(si_dims), c_int32,
                                         c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p,
                                         c_void_p, c_size_t, c_void_p]
+    L.si_fused_workspace_bytes.restype = c_size_t
+    L.si_fused_workspace_bytes.argtypes = [POINTER(si_dims), c_int32, c_int32]
+    L.si_indexer_topk_fused.restype = c_int32
+    L.si_indexer_topk_fused.argtypes = [c_void_p, c_void_p, c_void_p, POINTER(si_dims), c_int32,
+                                        c_int32, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
+                                        c_size_t, c_void_p]
     L.si_score_tile.restype = c_int32
     L.si_score_tile.argtypes = [c_void_p, c_void_p, c_void_p, POINTER(si_dims), c_int32, c_int32,
                                 c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p]
@@ -171,6 +178,21 @@ def si_indexer_topk_tiled(q, K, w, m, k, mask_mode, c_S, c_T, out_idx, out_score
         _dev_ptr(out_idx, torch.int32, "out_idx"), _dev_ptr(out_score, torch.float32, "out_score"),
         _dev_ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
         _stream_handle(stream)), "si_indexer_topk_tiled")
+
+
+def si_fused_workspace_bytes(B, S, H_I, D, T, k, c_S=0) -> int:
+    return int(load().si_fused_workspace_bytes(byref(si_dims(B, S, H_I, D, T)), k, c_S))
+
+
+def si_indexer_topk_fused(q, K, w, m, k, mask_mode, c_S, out_idx, out_score, workspace, stream=None):
+    dims = _dims_of(q, K, w)
+    _expect_out(out_idx, out_score, (dims.B, dims.S, k))
+    _check(load().si_indexer_topk_fused(
+        _dev_ptr(q, torch.bfloat16, "q"), _dev_ptr(K, torch.bfloat16, "K"),
+        _dev_ptr(w, torch.float32, "w"), byref(dims), m, k, mask_mode, c_S,
+        _dev_ptr(out_idx, torch.int32, "out_idx"), _dev_ptr(out_score, torch.float32, "out_score"),
+        _dev_ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
+        _stream_handle(stream)), "si_indexer_topk_fused")
 
 
 def si_score_tile(q, K, w, m, mask_mode, s0, t0, c_S, c_T, tile, stream=None):

@@ -12,7 +12,7 @@ INCLUDE = os.path.join(ROOT, "include")
 OBJ_DIR = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libstreamindex.so")
 
-SOURCES = ["score_tile.hip", "topk.hip", "driver.hip"]
+SOURCES = ["score_tile.hip", "fused.hip", "topk.hip", "driver.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",

@@ -109,6 +109,30 @@ int64_t next_width(int64_t t0, int64_t c_T, int64_t k) {
     return std::min<int64_t>(w, c_T);
 }
 
+// Workspace of the single-pass schedule: one launch counter per query tile, then the row
+// buffers of the resident workgroups.
+struct FusedLayout {
+    int32_t* counters;
+    int64_t n_launches;
+    RowBuffers slots;
+    size_t bytes;
+};
+FusedLayout carve_fused(void* base, int64_t S, int64_t k, int64_t c_S) {
+    FusedLayout L;
+    char* p = static_cast<char*>(base);
+    L.n_launches = (S + c_S - 1) / c_S;
+    size_t off = 0;
+    L.counters = reinterpret_cast<int32_t*>(p + off);
+    off = align_up(off + static_cast<size_t>(L.n_launches) * sizeof(int32_t), 256);
+    L.slots.keys = reinterpret_cast<key64_t*>(p + off);
+    L.slots.cap = static_cast<int32_t>(kFusedTriggerMul * k + 384);
+    off = align_up(off + static_cast<size_t>(kFusedSlots) * kQueriesPerBlock * L.slots.cap * sizeof(key64_t), 256);
+    L.slots.count = nullptr;
+    L.slots.theta = nullptr;
+    L.slots.bytes = off;
+    L.bytes = off;
+    return L;
+}
 }  // namespace
 
 // Per query row of a tile: a key buffer of 2k + c_T slots (a row is cut back to k as soon as
@@ -257,6 +281,42 @@ si_status si_indexer_topk(const void* q, const void* K, const float* w, const si
     if (st != SI_OK) return st;
     return si_indexer_topk_tiled(q, K, w, dims, m, k, mask_mode, plan.c_S, plan.c_T, out_idx,
                                  out_score, workspace, workspace_bytes, stream);
+}
+
+size_t si_fused_workspace_bytes(const si_dims* dims, int32_t k, int32_t c_S) {
+    if (!dims || dims->S < 1 || k < 1 || k > kFusedMaxK) return 0;
+    if (c_S < 1 || c_S > dims->S) c_S = dims->S;
+    return carve_fused(nullptr, dims->S, k, c_S).bytes;
+}
+
+si_status si_indexer_topk_fused(const void* q, const void* K, const float* w, const si_dims* dims,
+                                int32_t m, int32_t k, si_mask_mode mask_mode, int32_t c_S,
+                                int32_t* out_idx, float* out_score, void* workspace,
+                                size_t workspace_bytes, void* stream) {
+    si_status st = check_dims(dims, m, k, mask_mode);
+    if (st != SI_OK) return st;
+    if (k > kFusedMaxK) return SI_ERR_UNSUPPORTED_SHAPE;
+    if (!q || !K || !w || !out_idx || !out_score || !workspace) return SI_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return SI_ERR_INVALID_ARG;
+    const si_dims d = *dims;
+    if (c_S < 1 || c_S > d.S) c_S = d.S;
+    const FusedLayout L = carve_fused(workspace, d.S, k, c_S);
+    if (L.bytes > workspace_bytes) return SI_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    hipError_t e = timed(kProfInit, hs, [&] {
+        return launch_zero_ints(L.counters, static_cast<int32_t>(L.n_launches), hs);
+    });
+    if (e != hipSuccess) return hip_fail(e);
+    int64_t launch = 0;
+    for (int64_t s0 = 0; s0 < d.S; s0 += c_S, ++launch) {
+        const int32_t rows = static_cast<int32_t>(std::min<int64_t>(c_S, d.S - s0));
+        e = timed(kProfFused, hs, [&] {
+            return launch_fused(q, K, w, d, m, mask_mode, k, static_cast<int32_t>(s0), rows, L.slots,
+                                kFusedSlots, L.counters + launch, out_idx, out_score, hs);
+        });
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return SI_OK;
 }
 
 si_status si_topk_from_scores(const float* scores, int32_t R, int32_t n_cols,

@@ -1,0 +1,187 @@
+// Single-pass schedule of Algorithm 2: one persistent workgroup takes 8 consecutive queries
+// through their whole legal key range and does every step of the stream for them without
+// leaving the kernel -- score sweep with the mask and threshold filter in registers, the
+// merge (cutting a row back to its best k whenever it has collected 2k candidates) and the
+// final exact cut, sort and write-out (Section 4.2 for the pad).  Compared with the tiled
+// schedule the query operand is read once, there are no per-tile launches, a row's threshold
+// is refreshed as soon as 2k candidates have accumulated, and the only scratch memory is one
+// short row buffer per resident wave (tens of MB in total, L2 resident), independent of S.
+// By the corollary of Section 4.3 the result is the same exact top-k under the total order of
+// Section 4.1, so the output is bit-identical to the tiled schedule's.
+//
+// One wave owns one query row, as in the score sweep; the merge and the write-out are the
+// wave-level routines of topk_wave.h, so no step needs an atomic or a cross-wave exchange.
+// The only workgroup-wide decisions are "next work item" and "stop the sweep for a merge".
+
+#include "score_sweep.h"
+#include "topk_wave.h"
+
+namespace si {
+
+// A sweep is stopped once a row holds `trigger` keys and can overshoot by 319 (see score_sweep).
+__host__ __device__ inline int fused_trigger(int k) { return kFusedTriggerMul * k; }
+__host__ __device__ inline int fused_row_cap(int k) { return fused_trigger(k) + 384; }
+constexpr int kFusedRegKeys = (kFusedTriggerMul * kFusedMaxK + 384 + 63) / 64;  // a whole row in registers
+constexpr int kFusedSortLds = kWaves * (kFusedMaxK + kFusedMaxK / 8) * 8;
+
+template <int D>
+constexpr int fused_lds_bytes() {
+    return sweep_lds_bytes<D>() > kFusedSortLds ? sweep_lds_bytes<D>() : kFusedSortLds;
+}
+
+// Queries [s_begin, s_begin + rows) of every batch; work item = (batch, group of 8 queries),
+// handed out through *counter (zero before the launch), longest key range first so that the
+// workgroups running at any time have nearly equal work and walk the keys roughly together
+// (which keeps the key rows they share in L2).  Workgroup j uses rows [8j, 8j+8) of `slots`.
+template <int D, int HB>
+__global__ __launch_bounds__(kScoreThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ K,
+                          const float* __restrict__ w, int B, int S, int H, int T, int m,
+                          int mask_mode, int k, int pow2_k, int s_begin, int rows, RowBuffers slots,
+                          int* __restrict__ counter, int32_t* __restrict__ out_idx,
+                          float* __restrict__ out_score) {
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[fused_lds_bytes<D>()];
+    __shared__ int s_hist[kWaves][256];
+    __shared__ int s_flags[2 * kWaves];
+    __shared__ int s_item;
+
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int n_groups = (rows + kQB - 1) / kQB;
+    const int n_items = n_groups * B;
+    const int trigger = fused_trigger(k);
+    const int limit = compact_limit(k);
+    key64_t* const cand = slots.keys + (static_cast<int64_t>(blockIdx.x) * kQB + wave) * slots.cap;
+
+    for (;;) {
+        if (threadIdx.x == 0) s_item = atomicAdd(counter, 1);
+        if (threadIdx.x < 2 * kWaves) s_flags[threadIdx.x] = 0;
+        __syncthreads();
+        const int item = s_item;
+        __syncthreads();  // everybody has read s_item before the next round overwrites it
+        if (item >= n_items) break;  // uniform: every wave of every workgroup ends here
+        const int b = item % B;
+        const int r_first = (n_groups - 1 - item / B) * kQB;
+        const int r = r_first + wave;
+        const bool live = r < rows;
+        const int r_last = min(rows, r_first + kQB) - 1;
+        const int group_keys = legal_count(s_begin + r_last, T, m, mask_mode);  // uniform
+        const int row_keys = live ? legal_count(s_begin + r, T, m, mask_mode) : 0;
+        const int64_t qrow = static_cast<int64_t>(b) * S + s_begin + (live ? r : rows - 1);
+
+        SweepOut o;
+        o.theta = -__builtin_huge_valf();
+        o.cand = cand;
+        o.cap = slots.cap;
+        o.n_cand = 0;
+        o.live = live;
+        o.out_row = nullptr;
+        for (int kbeg = 0; kbeg < group_keys;) {
+            {
+                bf16x8 a[HB][D / 16];
+                float wr[HB][16];
+                // (re)loaded for every sweep: the merge in between needs the registers.  The row
+                // is made opaque so that the address arithmetic is redone here instead of being
+                // kept live across the sweep.
+                int64_t qrow_now = qrow;
+                asm volatile("" : "+s"(qrow_now));
+                load_query<D, HB>(q, w, qrow_now, H, a, wr);
+                o.row_keys = row_keys - kbeg;
+                o.index0 = static_cast<uint32_t>(kbeg);
+                const __bf16* Kb = K + (static_cast<int64_t>(b) * T + kbeg) * D;
+                kbeg += score_sweep<D, HB, true, true>(lds, a, wr, Kb, T - kbeg, group_keys - kbeg, o,
+                                                       s_flags, trigger);
+            }
+            __syncthreads();  // the sweep's LDS and flags are free again
+            if (kbeg >= group_keys) break;
+            // Merge: the sweep stopped because some row reached the trigger.  Every row that
+            // holds more than it would keep is cut back now, which also refreshes its threshold.
+            if (threadIdx.x < 2 * kWaves) s_flags[threadIdx.x] = 0;
+            if (o.n_cand > limit) {
+                RegKeys<kFusedRegKeys> keys;
+                keys.load(cand, o.n_cand);
+                int kept = 0;
+                const key64_t thr = wave_radix_kth(keys, k, limit, s_hist[wave], &kept);
+                wave_keep(keys, thr, cand, slots.cap);
+                o.n_cand = kept;
+                o.theta = fmaxf(o.theta, key_score(thr));
+            }
+            __builtin_amdgcn_s_waitcnt(0x0F70);  // the kept keys are written before anything is appended behind them
+            __syncthreads();
+        }
+
+        // Write-out: exact cut to k, sort best first in the wave's slice of the (now idle)
+        // sweep LDS, decode, pad.
+        if (live) {
+            key64_t* s_sort = reinterpret_cast<key64_t*>(lds) + static_cast<size_t>(wave) * sort_slots(pow2_k);
+            const SortSlot slot;
+            const int n = o.n_cand;
+            const int c = min(n, k);
+            {
+                RegKeys<kFusedRegKeys> keys;
+                keys.load(cand, n);
+                key64_t thr = 0ull;
+                int kept = 0;
+                if (n > k) thr = wave_radix_kth(keys, k, k, s_hist[wave], &kept);  // limit k: exact
+                wave_keep(keys, thr, s_sort, pow2_k, slot);
+            }
+            int P = 16;
+            while (P < c) P <<= 1;
+            for (int i = c + lane; i < P; i += 64) s_sort[slot(i)] = 0ull;  // empty keys sort last
+            __builtin_amdgcn_wave_barrier();
+            wave_sort_descending(s_sort, P);
+            const int64_t out = (static_cast<int64_t>(b) * S + s_begin + r) * k;
+            for (int j = lane; j < k; j += 64) {
+                if (j < c) {
+                    const key64_t key = s_sort[slot(j)];
+                    out_idx[out + j] = key_index(key);
+                    out_score[out + j] = key_score(key);
+                } else {  // Section 4.2: pad
+                    out_idx[out + j] = -1;
+                    out_score[out + j] = -__builtin_huge_valf();
+                }
+            }
+        }
+        __syncthreads();  // the next item's sweep overwrites the LDS the sort used
+    }
+}
+
+__global__ void zero_ints_kernel(int* p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+hipError_t launch_zero_ints(int32_t* p, int32_t n, hipStream_t stream) {
+    hipLaunchKernelGGL(zero_ints_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, p, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_fused(const void* q, const void* K, const float* w, const si_dims& d, int32_t m,
+                        int32_t mask_mode, int32_t k, int32_t s_begin, int32_t rows,
+                        const RowBuffers& slots, int32_t n_slots, int32_t* counter, int32_t* out_idx,
+                        float* out_score, hipStream_t stream) {
+    if (k < 1 || k > kFusedMaxK || slots.cap < fused_row_cap(k) || n_slots < 1) return hipErrorInvalidValue;
+    const int64_t items = static_cast<int64_t>((rows + kQB - 1) / kQB) * d.B;
+    const dim3 grid(static_cast<unsigned>(std::min<int64_t>(items, n_slots)));
+    const dim3 block(kScoreThreads);
+    const __bf16* qp = static_cast<const __bf16*>(q);
+    const __bf16* Kp = static_cast<const __bf16*>(K);
+    const int HB = (d.H_I + 31) / 32;
+    int pow2_k = 16;
+    while (pow2_k < k) pow2_k <<= 1;
+#define SI_LAUNCH(DD, HH)                                                                          \
+    hipLaunchKernelGGL((indexer_fused_kernel<DD, HH>), grid, block, 0, stream, qp, Kp, w, d.B, d.S, \
+                       d.H_I, d.T, m, mask_mode, k, pow2_k, s_begin, rows, slots, counter, out_idx, \
+                       out_score)
+    if (d.D == 128 && HB == 2) SI_LAUNCH(128, 2);
+    else if (d.D == 128 && HB == 1) SI_LAUNCH(128, 1);
+    else if (d.D == 64 && HB == 2) SI_LAUNCH(64, 2);
+    else if (d.D == 64 && HB == 1) SI_LAUNCH(64, 1);
+    else if (d.D == 32 && HB == 2) SI_LAUNCH(32, 2);
+    else if (d.D == 32 && HB == 1) SI_LAUNCH(32, 1);
+    else return hipErrorInvalidValue;
+#undef SI_LAUNCH
+    return hipGetLastError();
+}
+
+}  // namespace si

@@ -1,0 +1,282 @@
+// The key sweep of the fused score kernel (Section 5, "fused score kernel"; Section 1 for the
+// formula):
+//   score[t, s] = sum_h w[t,h] * max(0, sum_d q[t,h,d] * K[s,d])
+// for the 8 queries of one workgroup against a run of consecutive keys.  bf16 operands, fp32
+// MFMA accumulation, ReLU and the weighted head sum done on the MFMA result registers; the
+// per-head values never leave the wave.
+//
+// Mapping (gfx950, wave64, v_mfma_f32_32x32x16_bf16):
+//   - one wave owns one query for the whole key sweep.  The query's heads are the M side of
+//     the MFMA (32 heads per block, HB blocks), kept in registers: HB * D/16 operands of
+//     8 bf16.  Keys are the N side, 32 per MFMA, read from LDS.
+//   - the 32x32 result puts one key per lane column (lane & 31) and 16 heads per lane, so the
+//     head sum is 16 in-lane FMAs per head block plus one exchange between lane and lane^32.
+//   - a workgroup is 8 waves = 8 consecutive queries sharing each staged block of 128 keys.
+//     Key blocks travel HBM/L2 -> LDS directly (global_load_lds, no register round trip) into
+//     a ring of three buffers, two blocks ahead of the one being multiplied.
+//   - the loop is a software pipeline over 32-key sub-blocks: MFMAs of sub-block g, epilogue
+//     of sub-block g-1 and LDS reads for sub-block g+1 are interleaved instruction by
+//     instruction, so the matrix pipe, the vector ALU and the LDS work at the same time.
+// Every (query, key) score is produced by the same instruction sequence wherever the pair
+// falls in a sweep, which is what makes results independent of the tiling.
+//
+// Two outputs, chosen at compile time:
+//   dense  : the fp32 scores themselves (entry point si_score_tile);
+//   filter : the per-tile mask (Section 5) and the first half of the per-tile select are
+//            applied in registers: only legal entries that beat the row's threshold (the k-th
+//            best score of an earlier prefix of the key axis) are appended, as 64-bit
+//            (score, ~index) keys, to the row's buffer.  An entry that does not beat it can
+//            never enter the final top-k: keys are visited in ascending index order, so on
+//            equal score the entry already held has the smaller index and wins
+//            (Section 4.1).  One wave owns one row, so the append needs no atomics.
+#pragma once
+
+#include "si_internal.h"
+
+namespace si {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kWaves = 8;            // waves per workgroup, one query each
+constexpr int kQB = kWaves;          // queries per workgroup
+constexpr int kKeyChunk = 128;       // keys per LDS buffer
+constexpr int kScoreThreads = 64 * kWaves;
+constexpr int kLdsBuffers = 3;
+
+// LDS bytes the sweep needs for head dimension D (1 KiB aligned).
+template <int D>
+constexpr int sweep_lds_bytes() { return kLdsBuffers * kKeyChunk * D * 2; }
+
+// max(x, 0) on the bit pattern: negative floats (and -0) are negative integers.
+__device__ inline float relu(float x) { return __int_as_float(max(__float_as_int(x), 0)); }
+
+// Query operand of this wave: head h = hb*32 + col, d = ks*16 + half*8 .. +8, plus the head
+// weights in the layout of the MFMA result.  `qrow` is the query's row in q [B*S, H, D] and
+// w [B*S, H].  A head slot past H reuses head H-1 with weight 0, which adds exactly +0.
+template <int D, int HB>
+__device__ __forceinline__ void load_query(const __bf16* __restrict__ q, const float* __restrict__ w,
+                                           int64_t qrow, int H, bf16x8 (&a)[HB][D / 16],
+                                           float (&wr)[HB][16]) {
+    constexpr int KS = D / 16;
+    const int lane = threadIdx.x & 63;
+    const int col = lane & 31;
+    const int half = lane >> 5;
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) {
+        const int h = min(hb * 32 + col, H - 1);
+        const __bf16* src = q + (qrow * H + h) * D + half * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) a[hb][ks] = *reinterpret_cast<const bf16x8*>(src + ks * 16);
+        // Result register j of this lane holds head hb*32 + 8*(j/4) + 4*half + j%4.
+        float wv[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {  // all loads first, so that they overlap
+            const int hh = hb * 32 + 8 * (j >> 2) + 4 * half + (j & 3);
+            wv[j] = w[qrow * H + min(hh, H - 1)];
+        }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int hh = hb * 32 + 8 * (j >> 2) + 4 * half + (j & 3);
+            float v = hh < H ? wv[j] : 0.0f;
+            asm volatile("" : "+v"(v));  // keep the masked weight in a register for the whole sweep
+            wr[hb][j] = v;
+        }
+    }
+}
+
+// What the sweep does with the scores of this wave's query.
+struct SweepOut {
+    // filter mode
+    int row_keys;      // this row's legal keys inside the sweep (keys >= row_keys are dropped)
+    float theta;       // a key is appended only if its score beats this
+    key64_t* cand;     // the row's buffer
+    int cap;           // its capacity; an append past it is dropped (cannot happen when the
+                       // caller sizes the buffer as documented, kept as a bounds check)
+    int n_cand;        // keys held (in/out)
+    uint32_t index0;   // key index of the sweep's first key
+    // dense mode
+    bool live;         // false: this wave's row does not exist, store nothing
+    float* out_row;    // fp32 scores of the sweep's keys
+};
+
+// Sweeps keys [0, n_keys) of Kb (a multiple of 128 is covered: key rows past `key_clamp - 1`
+// repeat that row and are never emitted).  All 8 waves of the workgroup must call it together
+// with the same Kb, key_clamp and n_keys > 0.
+//
+// STOPPABLE (filter mode): the sweep also ends, for the whole workgroup at the same key, once
+// some wave holds at least `trigger` keys.  Each wave posts that condition in `flags`
+// (LDS, [2][kWaves] ints, zero on entry) after a 128-key step, and everybody reads the flags
+// of the previous step behind the step's barrier, so the decision is uniform without another
+// barrier.  A row can therefore grow to at most trigger + 319 keys before the sweep returns.
+//
+// Returns the number of keys swept (a multiple of 128, or >= n_keys at the natural end).  On
+// return every global -> LDS transfer the workgroup issued has landed for the calling wave;
+// a workgroup barrier must follow before the LDS is reused.
+template <int D, int HB, bool FILTER, bool STOPPABLE>
+__device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)[HB][D / 16],
+                                           const float (&wr)[HB][16], const __bf16* __restrict__ Kb,
+                                           int key_clamp, int n_keys, SweepOut& o, int* flags,
+                                           int trigger) {
+    static_assert(!STOPPABLE || FILTER, "only the filtering sweep can be stopped");
+    constexpr int KS = D / 16;             // MFMA steps along d
+    constexpr int EPM = 16 / KS;           // epilogue elements handled next to one MFMA
+    static_assert(16 % KS == 0, "epilogue elements must split evenly over the MFMA steps");
+    // LDS key rows are unpadded (2*D bytes); the 16-byte pieces of a row are XOR-swizzled so
+    // that the 16 lanes served together by one ds_read_b128 hit 16 different bank groups:
+    // piece p of row r sits in slot p ^ swz(r), swz(r) = (r / rows per 256 B) mod pieces per row.
+    constexpr int kRowBytes = D * 2;
+    constexpr int kPieces = D / 8;         // 16-byte pieces per key row
+    constexpr int kRowsPer256 = 256 / kRowBytes;
+    constexpr int kBufBytes = kKeyChunk * kRowBytes;
+    constexpr int kRowsPerLoad = 64 / kPieces;  // key rows covered by one wave-wide 1 KiB load
+    constexpr int kLoads = kKeyChunk / kRowsPerLoad / kWaves;  // loads per wave per chunk
+    static_assert(kKeyChunk % (kRowsPerLoad * kWaves) == 0, "chunk must split evenly over the waves");
+    static_assert(kKeyChunk == 128, "the pipelined loop is written for 4 sub-blocks per chunk");
+
+    // wave-uniform values live in scalar registers
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int col = lane & 31;
+    const int half = lane >> 5;
+    const int row_keys = o.row_keys;
+    const float theta = o.theta;
+    key64_t* const cand = o.cand;
+    const int cap = o.cap;
+    int n_cand = o.n_cand;
+    const uint32_t index0 = o.index0;
+    const bool live = o.live;
+    float* const out_row = o.out_row;
+
+    // Global -> LDS without a register round trip: each wave-wide load writes 1 KiB of LDS
+    // (lane l to byte l*16 of the block); the lane picks the global piece that belongs there.
+    typedef __attribute__((address_space(3))) void lds_void;
+    typedef __attribute__((address_space(1))) const void gbl_void;
+#define SI_FETCH(KC0, BUFOFF)                                                                      \
+    _Pragma("unroll") for (int i = 0; i < kLoads; ++i) {                                            \
+        const int blk = wave * kLoads + i;                   /* 1 KiB block inside the chunk */     \
+        const int row = blk * kRowsPerLoad + lane / kPieces; /* key row inside the chunk */         \
+        const int piece = (lane % kPieces) ^ ((row / kRowsPer256) % kPieces);                       \
+        const int key = min((KC0) + row, key_clamp - 1); /* rows past the edge repeat the last key */ \
+        const __bf16* src = Kb + static_cast<int64_t>(key) * D + piece * 8;                         \
+        __builtin_amdgcn_global_load_lds((gbl_void*)(src),                                          \
+            (lds_void*)(lds + (BUFOFF) + blk * 1024), 16, 0, 0);                                    \
+    }
+
+    // This lane's byte offset, inside a 32-key sub-block, of the operand for MFMA step ks.
+    const int swz = (col / kRowsPer256) % kPieces;
+    int koff[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) koff[ks] = col * kRowBytes + (((ks * 2 + half) ^ swz) * 16);
+#define SI_KREAD(BYTEOFF, KSTEP) \
+    (*reinterpret_cast<const bf16x8*>(lds + (BYTEOFF) + koff[KSTEP]))
+
+    // Chunks 0 and 1 in flight; chunk 0 must have landed before its first read.
+    int off_cur = 0, off_next = kBufBytes, off_nn = 2 * kBufBytes;  // LDS buffers: being read, next, filling
+    SI_FETCH(0, off_cur)
+    SI_FETCH(kKeyChunk, off_next)
+    __builtin_amdgcn_s_waitcnt(0x0F70 | kLoads);  // vmcnt(kLoads): everything but chunk 1 has landed
+    __syncthreads();
+
+    bf16x8 bq[KS];  // key operand of the sub-block about to be multiplied
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) bq[ks] = SI_KREAD(off_cur, ks);
+
+    // Software pipeline, one step per 32-key sub-block: the MFMAs of sub-block g fill one
+    // accumulator set while the ReLU / weight / head-sum epilogue drains the other one (sub-block
+    // g-1), and the key operand of sub-block g+1 is read from LDS into the registers the MFMAs
+    // have just consumed.  The scheduling barriers pin this interleaving: per MFMA, 16/KS epilogue
+    // elements and (in the last head block) one LDS read.  Each head block's KS MFMAs are issued
+    // back to back as one dependent accumulator chain, which measured slightly faster than
+    // alternating the head blocks.
+    floatx16 accA[HB], accB[HB];
+    const floatx16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb) accB[hb] = zero16;
+#define SI_STEP(CUR, PREV, OUT, NEXT_BYTEOFF)                                                      \
+    {                                                                                               \
+        float s_ = 0.0f;                                                                            \
+        _Pragma("unroll") for (int hb = 0; hb < HB; ++hb)                                           \
+            _Pragma("unroll") for (int ks = 0; ks < KS; ++ks) {                                     \
+                CUR[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[hb][ks], bq[ks],                \
+                                                                  ks == 0 ? zero16 : CUR[hb], 0, 0, 0); \
+                _Pragma("unroll") for (int e = (hb * KS + ks) * EPM; e < (hb * KS + ks + 1) * EPM; ++e)   \
+                    s_ = fmaf(wr[e / 16][e % 16], relu(PREV[e / 16][e % 16]), s_);                  \
+                if (hb == HB - 1) bq[ks] = SI_KREAD(NEXT_BYTEOFF, ks);                              \
+                __builtin_amdgcn_sched_barrier(0);                                                  \
+            }                                                                                       \
+        OUT = s_ + __shfl_xor(s_, 32);                                                              \
+    }
+    // 64 finished scores (lane l holds key KEY0 + l): append the kept ones / store them.
+#define SI_EMIT(VAL, KEY0)                                                                         \
+    {                                                                                               \
+        const int key = (KEY0) + lane;                                                              \
+        if (FILTER) {                                                                               \
+            const bool keep = key >= 0 && key < row_keys && (VAL) > theta;                          \
+            const unsigned long long mask = __ballot(keep);                                         \
+            if (mask != 0ull) {                                                                     \
+                const int below = __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(mask >> 32),      \
+                                  __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(mask), 0u));      \
+                if (keep && n_cand + below < cap)                                                   \
+                    cand[n_cand + below] = make_key((VAL), index0 + static_cast<uint32_t>(key));    \
+                n_cand += __popcll(mask);                                                           \
+            }                                                                                       \
+        } else if (live && key >= 0 && key < n_keys) {                                              \
+            out_row[key] = (VAL);                                                                   \
+        }                                                                                           \
+    }
+
+    float r_even = 0.0f;  // epilogue result of the last even sub-block, waiting for its odd partner
+    int kc0 = 0;
+    bool stop = false;
+    for (; kc0 < n_keys && !stop; kc0 += kKeyChunk) {
+        // Chunk kc0/128 + 2 starts its trip to LDS.  Issued unconditionally (addresses are clamped,
+        // the buffer is unused if the chunk does not exist) so that the vmcnt arithmetic below holds.
+        SI_FETCH(kc0 + 2 * kKeyChunk, off_nn)
+        float sp, s0v, s1v, s2v;
+        SI_STEP(accA, accB, sp, off_cur + 1 * 32 * kRowBytes)
+        SI_STEP(accB, accA, s0v, off_cur + 2 * 32 * kRowBytes)
+        SI_STEP(accA, accB, s1v, off_cur + 3 * 32 * kRowBytes)
+        // The next chunk must be in LDS, and visible to every wave, before its first read below.
+        __builtin_amdgcn_s_waitcnt(0x0F70 | kLoads);  // vmcnt(kLoads): only the newest chunk may be in flight
+        __syncthreads();
+        int posted = 0;
+        if (STOPPABLE) {  // what the waves posted after the previous step
+            const int* f = flags + (((kc0 / kKeyChunk) + 1) & 1) * kWaves;
+#pragma unroll
+            for (int i = 0; i < kWaves; ++i) posted |= f[i];
+        }
+        SI_STEP(accB, accA, s2v, off_next)
+        // even sub-blocks stay in the low half-wave, odd ones in the high half
+        const float res_prev = half ? sp : r_even;   // keys kc0 - 64 + lane (previous chunk)
+        const float res_cur = half ? s1v : s0v;      // keys kc0 + lane
+        r_even = s2v;
+        if (!FILTER || __ballot((res_prev > theta) | (res_cur > theta)) != 0ull) {
+            SI_EMIT(res_prev, kc0 - 64)
+            SI_EMIT(res_cur, kc0)
+        }
+        if (STOPPABLE) {
+            if (lane == 0) flags[((kc0 / kKeyChunk) & 1) * kWaves + wave] = n_cand >= trigger ? 1 : 0;
+            stop = __builtin_amdgcn_readfirstlane(posted) != 0;
+        }
+        const int t_ = off_cur; off_cur = off_next; off_next = off_nn; off_nn = t_;
+    }
+    {   // drain: the last sub-block's epilogue and the last 64 scores
+        float s_ = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 16 * HB; ++e) s_ = fmaf(wr[e / 16][e % 16], relu(accB[e / 16][e % 16]), s_);
+        const float sp = s_ + __shfl_xor(s_, 32);
+        const float res_prev = half ? sp : r_even;
+        SI_EMIT(res_prev, kc0 - 64)
+    }
+#undef SI_STEP
+#undef SI_EMIT
+#undef SI_FETCH
+#undef SI_KREAD
+    o.n_cand = n_cand;
+    // loads of chunks past the end may still be in flight: let them land before the LDS is reused
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    return kc0;
+}
+
+}  // namespace si

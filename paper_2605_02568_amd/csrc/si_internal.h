@@ -44,6 +44,13 @@ constexpr int kMaxK = 4096;
 constexpr int kMaxHeads = 64;
 constexpr int kQueriesPerBlock = 8;  // score kernel: one query per wave, 8 waves
 
+// Single-pass schedule (fused.hip): k up to kFusedMaxK; a row is merged once it holds
+// kFusedTriggerMul * k keys; at most kFusedSlots workgroups are resident (one per compute unit
+// of an MI355X), each with 8 row buffers.
+constexpr int kFusedMaxK = 1024;
+constexpr int kFusedTriggerMul = 2;
+constexpr int kFusedSlots = 256;
+
 // Per-row state of the current query tile, carved from the caller's workspace.
 struct RowBuffers {
     key64_t* keys;   // [rows, cap] unsorted
@@ -54,7 +61,7 @@ struct RowBuffers {
 };
 RowBuffers carve_workspace(void* base, int64_t rows, int64_t k, int64_t c_T);
 
-enum ProfileClass { kProfScore = 0, kProfFilterScores = 1, kProfCompact = 2, kProfFinalize = 3, kProfInit = 4 };
+enum ProfileClass { kProfScore = 0, kProfFilterScores = 1, kProfCompact = 2, kProfFinalize = 3, kProfInit = 4, kProfFused = 5 };
 
 // Kernel launchers (each enqueues exactly one kernel on `stream`).
 // Dense fp32 tile [B, tile_rows, tile_cols] of queries [s0, s0+rows) x keys [t0, t0+width).
@@ -77,5 +84,13 @@ hipError_t launch_compact(const RowBuffers& rb, int32_t B, int32_t rows, int32_t
 hipError_t launch_finalize(const RowBuffers& rb, int32_t B, int32_t rows, int32_t tile_rows, int32_t k,
                            int64_t out_batch_stride, int64_t out_row0, int32_t* out_idx,
                            float* out_score, hipStream_t stream);
+
+// Single-pass schedule: queries [s_begin, s_begin + rows) of every batch in one launch.
+// slots: n_slots * 8 row buffers of slots.cap >= 2k + 384 keys; *counter must be zero.
+hipError_t launch_fused(const void* q, const void* K, const float* w, const si_dims& d, int32_t m,
+                        int32_t mask_mode, int32_t k, int32_t s_begin, int32_t rows,
+                        const RowBuffers& slots, int32_t n_slots, int32_t* counter, int32_t* out_idx,
+                        float* out_score, hipStream_t stream);
+hipError_t launch_zero_ints(int32_t* p, int32_t n, hipStream_t stream);
 
 }  // namespace si

@@ -1,0 +1,88 @@
+"""GPU parity of the single-pass schedule (si_indexer_topk_fused): against the oracle, and
+bit-identical to the tiled schedule, on shapes that exercise the in-kernel merge (rows that
+collect several times 2k candidates), the launch split c_S, batches, both mask modes and the
+degenerate rows."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2605_02568_amd as P
+import workloads as W
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _rand_problem(seed, B, S, H, D, T):
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    q = torch.randn((B, S, H, D), generator=g).to(torch.bfloat16)
+    K = torch.randn((B, T, D), generator=g).to(torch.bfloat16)
+    w = torch.randn((B, S, H), generator=g) / np.sqrt(H)
+    return q, K, w
+
+
+def _run(fn_name, q, K, w, m, k, mask, *tiling):
+    B, S, H, D = q.shape
+    T = K.shape[1]
+    out_idx = torch.full((B, S, k), -7, dtype=torch.int32, device=DEV)
+    out_score = torch.full((B, S, k), 123.0, dtype=torch.float32, device=DEV)
+    if fn_name == "fused":
+        ws = torch.empty(P.si_fused_workspace_bytes(B, S, H, D, T, k, tiling[0]), dtype=torch.uint8, device=DEV)
+        P.si_indexer_topk_fused(q, K, w, m, k, mask, tiling[0], out_idx, out_score, ws)
+    else:
+        ws = torch.empty(P.si_workspace_bytes(B, S, H, D, T, k, *tiling), dtype=torch.uint8, device=DEV)
+        P.si_indexer_topk_tiled(q, K, w, m, k, mask, tiling[0], tiling[1], out_idx, out_score, ws)
+    torch.cuda.synchronize()
+    return out_idx, out_score
+
+
+def _same(a, b):
+    return torch.equal(a[0], b[0]) and torch.equal(a[1].view(torch.int32), b[1].view(torch.int32))
+
+
+@pytest.mark.parametrize("B,S,H,D,T,m,k,mask,c_S", [
+    (1, 256, 4, 32, 64, 4, 16, 1, 0),        # tiny head shape
+    (1, 37, 33, 64, 200, 1, 7, 0, 0),        # ragged group, two head blocks, no mask
+    (2, 203, 64, 128, 50, 4, 16, 1, 64),     # batch 2, ragged S, several launches
+    (1, 2048, 64, 128, 512, 4, 64, 1, 0),    # V4 head shape: rows merge several times
+    (1, 1500, 64, 128, 3000, 1, 1024, 1, 0), # largest k; rows collect > 2k candidates
+    (1, 640, 8, 32, 5000, 1, 1, 0, 256),     # k = 1
+    (3, 64, 31, 64, 900, 2, 100, 0, 0),      # k above and below the row lengths
+])
+def test_fused_matches_oracle_and_tiled(oracle, B, S, H, D, T, m, k, mask, c_S):
+    print(f"fused B={B} S={S} H={H} D={D} T={T} m={m} k={k} mask={mask} c_S={c_S}", flush=True)
+    q, K, w = _rand_problem(31 + S, B, S, H, D, T)
+    qd, Kd, wd = q.to(DEV), K.to(DEV), w.to(DEV)
+    fused = _run("fused", qd, Kd, wd, m, k, mask, c_S)
+    stats = parity.check_rows(
+        oracle, W.bf16_bits(q).reshape(B * S, H, D), w.numpy().reshape(B * S, H),
+        W.bf16_bits(K), np.repeat(np.arange(B, dtype=np.int32), S),
+        np.tile(np.arange(S, dtype=np.int64), B), m, k, mask,
+        fused[0].cpu().numpy().reshape(B * S, k), fused[1].cpu().numpy().reshape(B * S, k))
+    assert stats["min_recall"] >= 1.0 - 2.0 / k, stats
+    tiled = _run("tiled", qd, Kd, wd, m, k, mask, min(S, 128), min(T, 384))
+    assert _same(fused, tiled)
+
+
+def test_fused_adversarial_ascending_scores(oracle):
+    """Every later key scores higher for every query: nothing can be filtered, every row is
+    merged again after every k new keys."""
+    B, S, H, D, m, k = 1, 256, 1, 32, 1, 64
+    T = 6000
+    g = torch.Generator(device="cpu").manual_seed(10)
+    base = torch.randn((D,), generator=g).abs() + 0.1
+    q = (base[None, None, None, :] * (1.0 + torch.rand((B, S, H, D), generator=g))).to(torch.bfloat16)
+    scale = torch.linspace(0.5, 4.0, T)
+    K = (base[None, None, :] * scale[None, :, None]).to(torch.bfloat16)
+    w = torch.ones((B, S, H))
+    qd, Kd, wd = q.to(DEV), K.to(DEV), w.to(DEV)
+    fused = _run("fused", qd, Kd, wd, m, k, 0, 0)
+    tiled = _run("tiled", qd, Kd, wd, m, k, 0, S, 4096)
+    assert _same(fused, tiled)
+    stats = parity.check_rows(
+        oracle, W.bf16_bits(q).reshape(S, H, D), w.numpy().reshape(S, H), W.bf16_bits(K),
+        np.zeros(S, dtype=np.int32), np.arange(S, dtype=np.int64), m, k, 0,
+        fused[0].cpu().numpy().reshape(S, k), fused[1].cpu().numpy().reshape(S, k))
+    assert stats["mean_recall"] > 0.999, stats
