@@ -1,11 +1,12 @@
 #!/usr/bin/env python3
 """Benchmark of the indexer top-k hot path on one MI355X.
 
-A step is one pass of the whole path (score tiles, per-tile select, merge, write-out over
-every query and key tile) on one batch of seeded synthetic V4-Flash-shaped inputs that are
-already resident in HBM.  Prints ONE JSON line.
+A step is one pass of the whole path (score, mask, per-tile select, merge, write-out for every
+query against all its legal keys) on one batch of seeded synthetic V4-Flash-shaped inputs
+that are already resident in HBM.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload flash_1m] [--budget-gb 8]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload flash_1m]
+                  [--schedule auto|fused|tiled] [--budget-gb 8]
 """
 from __future__ import annotations
 
@@ -22,10 +23,10 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 
 
-def _traffic_from_profiles(workload: str):
-    """HBM bytes per score-tile launch measured with rocprofv3 --pmc (two runs), if a summary
-    for this workload has been committed under profiles/; else None."""
-    path = os.path.join(ROOT, "profiles", f"score_tile_{workload}_traffic.txt")
+def _traffic_from_profiles(kernel: str, workload: str):
+    """HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (two runs), if
+    a summary for this kernel and workload has been committed under profiles/; else None."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_traffic.txt")
     if not os.path.exists(path):
         return None
     for line in open(path):
@@ -41,8 +42,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="flash_1m")
     ap.add_argument("--budget-gb", type=float, default=8.0, help="HBM budget for the workspace")
-    ap.add_argument("--schedule", choices=["fused", "tiled"], default="tiled",
-                    help="fused: single-pass kernel (k <= 1024); tiled: one launch per (c_S x c_T) tile")
+    ap.add_argument("--schedule", choices=["auto", "fused", "tiled"], default="auto",
+                    help="fused: single-pass kernel (k <= 1024); tiled: one launch per (c_S x c_T) "
+                         "tile; auto: what si_indexer_topk picks (fused when it applies)")
     ap.add_argument("--c-s", type=int, default=0, help="explicit query tile (0 = planned)")
     ap.add_argument("--c-t", type=int, default=0, help="explicit key tile (0 = planned)")
     ap.add_argument("--oracle-rows", type=int, default=256,
@@ -78,7 +80,9 @@ def main() -> int:
 
     q, K, w, info = W.make_inputs(wl, device=dev)
     budget = int(args.budget_gb * 1e9)
-    fused = args.schedule == "fused"
+    fused = args.schedule == "fused" or (
+        args.schedule == "auto" and not (args.c_s and args.c_t)
+        and P.si_fused_workspace_bytes(wl.B, wl.S, wl.H, wl.D, T, wl.k, 0) > 0)
     if fused:
         c_S, c_T = (min(args.c_s, wl.S) if args.c_s else wl.S), 0
         ws_bytes = P.si_fused_workspace_bytes(wl.B, wl.S, wl.H, wl.D, T, wl.k, c_S)
@@ -155,7 +159,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {
             "workload": wl.name, "B": wl.B, "S": wl.S, "H_I": wl.H, "D": wl.D, "T": T, "m": wl.m,
-            "k": wl.k, "mask": "causal_block" if wl.mask_mode else "none", "schedule": args.schedule,
+            "k": wl.k, "mask": "causal_block" if wl.mask_mode else "none",
+            "schedule": "fused" if fused else "tiled",
             "c_S": c_S, "c_T": c_T,
             "seed": wl.seed, "sigma_w": info["sigma_w"],
         },
@@ -177,7 +182,7 @@ def main() -> int:
             "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s",
             "frac": achieved / PEAK_BF16_TFLOPS,
-            "traffic": _traffic_from_profiles(wl.name),
+            "traffic": _traffic_from_profiles("indexer_fused" if fused else "score_tile", wl.name),
             "flop_per_launch": flop_per_launch,
             "ms_per_launch": score_ms_per_launch,
         },

@@ -10,11 +10,15 @@
  *              (a,i) > (b,j)  <=>  a > b or (a == b and i < j)            (Section 4.1)
  *              listed best first; the remaining slots hold idx = -1, score = -inf.
  *
- * It is computed as the chunked partition-merge stream of Algorithm 2: queries in tiles of
- * c_S, keys in tiles of c_T, a running top-k buffer per query.  The [B,S,H,T] tensor is never
- * formed; the largest transient is one candidate list of at most c_T (score, index) pairs per
- * query of the current query tile, inside `workspace` (O(B * c_S * c_T) bytes).
- * The result does not depend on (c_S, c_T): it is bit-identical for every tiling.
+ * It is computed as the chunked partition-merge stream of Algorithm 2: keys are visited in
+ * chunks, a running top-k buffer per query absorbs each chunk's candidates.  The [B,S,H,T]
+ * tensor is never formed.  Two schedules of the same stream are offered:
+ *   tiled       one launch per (c_S x c_T) tile; the largest transient is one candidate list of
+ *               at most c_T (score, index) pairs per query of the current query tile, inside
+ *               `workspace` (O(B * c_S * c_T) bytes) -- the design-space axes of Section 6.5;
+ *   single pass one persistent kernel; 8 queries per workgroup walk their whole key range and
+ *               the only transient is a short row buffer per resident wave (tens of MB).
+ * The result does not depend on the schedule or on (c_S, c_T): it is bit-identical.
  *
  * Conventions for every entry point
  *   - q, K, w, out_idx, out_score, workspace and every other array argument marked "device"
@@ -82,8 +86,10 @@ si_status si_plan_tiles(const si_dims* dims, int32_t m, int32_t k, si_mask_mode 
  * count and an fp32 threshold; B*c_S rows (c_S, c_T clamped to S, T).  0 on invalid arguments. */
 size_t si_workspace_bytes(const si_dims* dims, int32_t k, int32_t c_S, int32_t c_T);
 
-/* The whole step (Algorithm 2) with the tiling chosen by si_plan_tiles for
- * budget = workspace_bytes.
+/* The whole step (Algorithm 2).  Runs the single-pass schedule (si_indexer_topk_fused, one
+ * launch) when k <= 1024 and workspace_bytes >= si_fused_workspace_bytes(dims, k, 0); otherwise
+ * the tiled schedule with the tiling si_plan_tiles chooses for budget = workspace_bytes.  Both
+ * give the same bits.
  *   q         device [B,S,H_I,D] bf16        K  device [B,T,D] bf16      w  device [B,S,H_I] f32
  *   out_idx   device [B,S,k] int32           out_score  device [B,S,k] f32
  *   workspace device, workspace_bytes bytes, 256-byte aligned */

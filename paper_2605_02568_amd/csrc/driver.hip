@@ -276,6 +276,12 @@ si_status si_indexer_topk(const void* q, const void* K, const float* w, const si
                           int32_t m, int32_t k, si_mask_mode mask_mode, int32_t* out_idx,
                           float* out_score, void* workspace, size_t workspace_bytes,
                           void* stream) {
+    // The single-pass schedule whenever it applies (k <= 1024) and its small workspace fits;
+    // otherwise the tiled schedule with the plan for this budget.
+    const size_t fused_bytes = si_fused_workspace_bytes(dims, k, 0);
+    if (fused_bytes != 0 && fused_bytes <= workspace_bytes)
+        return si_indexer_topk_fused(q, K, w, dims, m, k, mask_mode, 0, out_idx, out_score, workspace,
+                                     workspace_bytes, stream);
     si_plan plan;
     si_status st = si_plan_tiles(dims, m, k, mask_mode, workspace_bytes, &plan);
     if (st != SI_OK) return st;

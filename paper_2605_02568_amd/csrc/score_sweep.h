@@ -91,8 +91,9 @@ struct SweepOut {
     int row_keys;      // this row's legal keys inside the sweep (keys >= row_keys are dropped)
     float theta;       // a key is appended only if its score beats this
     key64_t* cand;     // the row's buffer
-    int cap;           // its capacity; an append past it is dropped (cannot happen when the
-                       // caller sizes the buffer as documented, kept as a bounds check)
+    int cap;           // its capacity; the survivors of a block of 64 scores are appended only if
+                       // all of them fit (always the case when the caller sizes the buffer as
+                       // documented; kept as a bounds check on wave-uniform values)
     int n_cand;        // keys held (in/out)
     uint32_t index0;   // key index of the sweep's first key
     // dense mode
@@ -214,11 +215,10 @@ __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)
         if (FILTER) {                                                                               \
             const bool keep = key >= 0 && key < row_keys && (VAL) > theta;                          \
             const unsigned long long mask = __ballot(keep);                                         \
-            if (mask != 0ull) {                                                                     \
+            if (mask != 0ull && n_cand + static_cast<int>(__popcll(mask)) <= cap) { /* always, see SweepOut */ \
                 const int below = __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(mask >> 32),      \
                                   __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(mask), 0u));      \
-                if (keep && n_cand + below < cap)                                                   \
-                    cand[n_cand + below] = make_key((VAL), index0 + static_cast<uint32_t>(key));    \
+                if (keep) cand[n_cand + below] = make_key((VAL), index0 + static_cast<uint32_t>(key)); \
                 n_cand += __popcll(mask);                                                           \
             }                                                                                       \
         } else if (live && key >= 0 && key < n_keys) {                                              \

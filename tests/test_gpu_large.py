@@ -58,6 +58,16 @@ def _run(wl, q, K, w, c_S, c_T, budget=None):
     return out_idx, out_score
 
 
+def _run_default(wl, q, K, w, nbytes):
+    """si_indexer_topk with a workspace of nbytes: the single-pass schedule for k <= 1024."""
+    out_idx = torch.empty((wl.B, wl.S, wl.k), dtype=torch.int32, device=DEV)
+    out_score = torch.empty((wl.B, wl.S, wl.k), dtype=torch.float32, device=DEV)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    P.si_indexer_topk(q, K, w, wl.m, wl.k, wl.mask_mode, out_idx, out_score, ws)
+    torch.cuda.synchronize()
+    return out_idx, out_score
+
+
 def _same_bits(a, b):
     return torch.equal(a[0], b[0]) and torch.equal(a[1].view(torch.int32), b[1].view(torch.int32))
 
@@ -77,6 +87,10 @@ def test_flash_64k_sampled_rows(oracle):
     # another tiling, including key tiles narrower than k: same bits
     other = _run(wl, q, K, w, 2048, 256)
     assert _same_bits(out, other)
+    # the single-pass schedule in its own small workspace: same bits
+    fused_bytes = P.si_fused_workspace_bytes(wl.B, wl.S, wl.H, wl.D, wl.T, wl.k)
+    assert 0 < fused_bytes < 64 * 2**20
+    assert _same_bits(out, _run_default(wl, q, K, w, fused_bytes))
 
 
 def test_flash_256k_key_tile_sweep_is_bit_identical(oracle):
@@ -93,6 +107,8 @@ def test_flash_256k_key_tile_sweep_is_bit_identical(oracle):
             assert stats["mean_recall"] > 0.9999 and stats["min_recall"] >= 1.0 - 2.0 / wl.k
         else:
             assert _same_bits(out, ref), c_T
+    _say("flash_256k single pass")
+    assert _same_bits(ref, _run_default(wl, q, K, w, P.si_fused_workspace_bytes(wl.B, wl.S, wl.H, wl.D, wl.T, wl.k)))
 
 
 def test_flash_1m_within_8gb_workspace(oracle):
@@ -108,3 +124,8 @@ def test_flash_1m_within_8gb_workspace(oracle):
     valid = (out[0][0] >= 0).sum(dim=1).cpu().numpy()
     t = np.arange(wl.S)
     assert np.array_equal(valid, np.minimum(wl.k, np.minimum(wl.T, (t + 1) // wl.m)))
+    # the single-pass schedule needs a few tens of MB instead: same bits
+    fused_bytes = P.si_fused_workspace_bytes(wl.B, wl.S, wl.H, wl.D, wl.T, wl.k)
+    _say(f"flash_1m single pass, workspace={fused_bytes}")
+    assert 0 < fused_bytes < 64 * 2**20
+    assert _same_bits(out, _run_default(wl, q, K, w, fused_bytes))

@@ -29,15 +29,23 @@ def _same(a, b):
     return torch.equal(a[0], b[0]) and torch.equal(a[1].view(torch.int32), b[1].view(torch.int32))
 
 
+@pytest.mark.parametrize("schedule", ["tiled", "single_pass"])
 @pytest.mark.parametrize("S,T,m,k", [(2048, 512, 4, 64), (1536, 1536, 1, 1024)])
-def test_side_stream_and_graph_replay(S, T, m, k):
-    print(f"streams S={S} T={T} m={m} k={k}", flush=True)
+def test_side_stream_and_graph_replay(S, T, m, k, schedule):
+    print(f"streams S={S} T={T} m={m} k={k} {schedule}", flush=True)
     q, K, w = _problem(11, S, T, k)
     c_S, c_T = 512, 384
-    ws = torch.empty(P.si_workspace_bytes(1, S, 64, 128, T, k, c_S, c_T), dtype=torch.uint8, device=DEV)
+    if schedule == "tiled":
+        ws = torch.empty(P.si_workspace_bytes(1, S, 64, 128, T, k, c_S, c_T), dtype=torch.uint8, device=DEV)
+        call = lambda oi, os_, stream=None: P.si_indexer_topk_tiled(  # noqa: E731
+            q, K, w, m, k, P.SI_MASK_CAUSAL_BLOCK, c_S, c_T, oi, os_, ws, stream=stream)
+    else:
+        ws = torch.empty(P.si_fused_workspace_bytes(1, S, 64, 128, T, k, c_S), dtype=torch.uint8, device=DEV)
+        call = lambda oi, os_, stream=None: P.si_indexer_topk_fused(  # noqa: E731
+            q, K, w, m, k, P.SI_MASK_CAUSAL_BLOCK, c_S, oi, os_, ws, stream=stream)
 
     eager = _outputs(S, k)
-    P.si_indexer_topk_tiled(q, K, w, m, k, P.SI_MASK_CAUSAL_BLOCK, c_S, c_T, eager[0], eager[1], ws)
+    call(eager[0], eager[1])
     torch.cuda.synchronize()
 
     # a side stream (default priority): the result is there once that stream is synchronised
@@ -45,8 +53,7 @@ def test_side_stream_and_graph_replay(S, T, m, k):
     on_side = _outputs(S, k)
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
-        P.si_indexer_topk_tiled(q, K, w, m, k, P.SI_MASK_CAUSAL_BLOCK, c_S, c_T, on_side[0], on_side[1],
-                                ws, stream=side)
+        call(on_side[0], on_side[1], stream=side)
     side.synchronize()
     assert _same(eager, on_side)
 
@@ -55,8 +62,7 @@ def test_side_stream_and_graph_replay(S, T, m, k):
     captured = _outputs(S, k)
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
-        P.si_indexer_topk_tiled(q, K, w, m, k, P.SI_MASK_CAUSAL_BLOCK, c_S, c_T, captured[0],
-                                captured[1], ws)
+        call(captured[0], captured[1])
     for replay in range(3):
         captured[0].fill_(-9)
         captured[1].fill_(-1.0)
@@ -66,6 +72,6 @@ def test_side_stream_and_graph_replay(S, T, m, k):
         torch.cuda.synchronize()
         assert _same(eager, captured), f"replay {replay}"
         again = _outputs(S, k)
-        P.si_indexer_topk_tiled(q, K, w, m, k, P.SI_MASK_CAUSAL_BLOCK, c_S, c_T, again[0], again[1], ws)
+        call(again[0], again[1])
         torch.cuda.synchronize()
         assert _same(eager, again)
