@@ -40,10 +40,16 @@ void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
                           int mask_mode, int k, int pow2_k, int s_begin, int rows, RowBuffers slots,
                           int* __restrict__ counter, int32_t* __restrict__ out_idx,
                           float* __restrict__ out_score) {
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[fused_lds_bytes<D>()];
-    __shared__ int s_hist[kWaves][256];
-    __shared__ int s_flags[2 * kWaves];
-    __shared__ int s_item;
+    // One LDS object for everything (sweep buffers / sort area, histograms, flags, work item):
+    // with several, the compiler orders every LDS read behind the global -> LDS transfers in
+    // flight and the key prefetch of the sweep no longer overlaps anything.
+    constexpr int kHistOff = fused_lds_bytes<D>();
+    constexpr int kFlagsOff = kHistOff + kWaves * 256 * 4;
+    constexpr int kItemOff = kFlagsOff + 2 * kWaves * 4;
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[kItemOff + 16];
+    int (*s_hist)[256] = reinterpret_cast<int (*)[256]>(lds + kHistOff);
+    int* s_flags = reinterpret_cast<int*>(lds + kFlagsOff);
+    int& s_item = *reinterpret_cast<int*>(lds + kItemOff);
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
@@ -80,12 +86,14 @@ void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
             {
                 bf16x8 a[HB][D / 16];
                 float wr[HB][16];
-                // (re)loaded for every sweep: the merge in between needs the registers.  The row
-                // is made opaque so that the address arithmetic is redone here instead of being
-                // kept live across the sweep.
+                // (re)loaded for every sweep: the merge in between needs the registers.  Row and
+                // lane are made opaque so that the address arithmetic is redone here instead of
+                // being kept live (spilled) across the sweep.
                 int64_t qrow_now = qrow;
                 asm volatile("" : "+s"(qrow_now));
-                load_query<D, HB>(q, w, qrow_now, H, a, wr);
+                int lane_now = lane;
+                asm volatile("" : "+v"(lane_now));
+                load_query<D, HB>(q, w, qrow_now, H, lane_now, a, wr);
                 o.row_keys = row_keys - kbeg;
                 o.index0 = static_cast<uint32_t>(kbeg);
                 const __bf16* Kb = K + (static_cast<int64_t>(b) * T + kbeg) * D;

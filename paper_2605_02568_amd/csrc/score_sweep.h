@@ -53,13 +53,13 @@ __device__ inline float relu(float x) { return __int_as_float(max(__float_as_int
 
 // Query operand of this wave: head h = hb*32 + col, d = ks*16 + half*8 .. +8, plus the head
 // weights in the layout of the MFMA result.  `qrow` is the query's row in q [B*S, H, D] and
-// w [B*S, H].  A head slot past H reuses head H-1 with weight 0, which adds exactly +0.
+// w [B*S, H]; `lane` is the caller's lane id.  A head slot past H reuses head H-1 with weight 0,
+// which adds exactly +0.
 template <int D, int HB>
 __device__ __forceinline__ void load_query(const __bf16* __restrict__ q, const float* __restrict__ w,
-                                           int64_t qrow, int H, bf16x8 (&a)[HB][D / 16],
+                                           int64_t qrow, int H, int lane, bf16x8 (&a)[HB][D / 16],
                                            float (&wr)[HB][16]) {
     constexpr int KS = D / 16;
-    const int lane = threadIdx.x & 63;
     const int col = lane & 31;
     const int half = lane >> 5;
 #pragma unroll
@@ -238,8 +238,15 @@ __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)
         SI_STEP(accB, accA, s0v, off_cur + 2 * 32 * kRowBytes)
         SI_STEP(accA, accB, s1v, off_cur + 3 * 32 * kRowBytes)
         // The next chunk must be in LDS, and visible to every wave, before its first read below.
-        __builtin_amdgcn_s_waitcnt(0x0F70 | kLoads);  // vmcnt(kLoads): only the newest chunk may be in flight
-        __syncthreads();
+        // A bare barrier: __syncthreads() would add a release fence that waits for every vector
+        // memory operation, i.e. also for the chunk that has just started its trip.  What the
+        // barrier must order is waited for explicitly -- vmcnt(kLoads): only the newest chunk may
+        // be in flight; lgkmcnt(0): this wave's LDS writes (the flags) are done -- and the empty
+        // asm statements keep the compiler from moving memory accesses across it.
+        __builtin_amdgcn_s_waitcnt(0x0070 | kLoads);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
         int posted = 0;
         if (STOPPABLE) {  // what the waves posted after the previous step
             const int* f = flags + (((kc0 / kKeyChunk) + 1) & 1) * kWaves;

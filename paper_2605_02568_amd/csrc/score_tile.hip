@@ -34,7 +34,7 @@ void score_tile_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ 
     bf16x8 a[HB][D / 16];
     float wr[HB][16];
     const int64_t qrow = static_cast<int64_t>(b) * S + s0 + (live ? r : rows - 1);
-    load_query<D, HB>(q, w, qrow, H, a, wr);
+    load_query<D, HB>(q, w, qrow, H, lane, a, wr);
 
     SweepOut o;
     o.row_keys = 0;
