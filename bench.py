@@ -84,7 +84,7 @@ def main() -> int:
         args.schedule == "auto" and not (args.c_s and args.c_t)
         and P.si_fused_workspace_bytes(wl.B, wl.S, wl.H, wl.D, T, wl.k, 0) > 0)
     if fused:
-        c_S, c_T = (min(args.c_s, wl.S) if args.c_s else wl.S), 0
+        c_S, c_T = (min(args.c_s, wl.S) if args.c_s else min(131072, wl.S)), 0
         ws_bytes = P.si_fused_workspace_bytes(wl.B, wl.S, wl.H, wl.D, T, wl.k, c_S)
     elif args.c_s and args.c_t:
         c_S, c_T = min(args.c_s, wl.S), min(args.c_t, T)

@@ -112,7 +112,9 @@ si_status si_indexer_topk_tiled(const void* q, const void* K, const float* w,
  * leaving the kernel.  No (c_S x c_T) candidate lists exist: the workspace holds one short row
  * buffer per resident wave plus one counter per launch, independent of S and T
  * (si_fused_workspace_bytes, about 40 MB at k = 1024).  Requires k <= 1024.
- * c_S = queries per kernel launch (<= 0 or > S: all of them in one launch). */
+ * c_S = queries per kernel launch (<= 0: the library's default, 131072; values above S are
+ * clamped).  The split only resynchronises the workgroups' walk over the keys; it does not
+ * change the result. */
 size_t si_fused_workspace_bytes(const si_dims* dims, int32_t k, int32_t c_S);
 si_status si_indexer_topk_fused(const void* q, const void* K, const float* w, const si_dims* dims,
                                 int32_t m, int32_t k, si_mask_mode mask_mode, int32_t c_S,

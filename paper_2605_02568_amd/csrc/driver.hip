@@ -117,6 +117,10 @@ struct FusedLayout {
     RowBuffers slots;
     size_t bytes;
 };
+int32_t fused_rows_per_launch(int32_t c_S, int32_t S) {
+    if (c_S < 1) c_S = kFusedDefaultRows;
+    return std::min(c_S, S);
+}
 FusedLayout carve_fused(void* base, int64_t S, int64_t k, int64_t c_S) {
     FusedLayout L;
     char* p = static_cast<char*>(base);
@@ -291,7 +295,7 @@ si_status si_indexer_topk(const void* q, const void* K, const float* w, const si
 
 size_t si_fused_workspace_bytes(const si_dims* dims, int32_t k, int32_t c_S) {
     if (!dims || dims->S < 1 || k < 1 || k > kFusedMaxK) return 0;
-    if (c_S < 1 || c_S > dims->S) c_S = dims->S;
+    c_S = fused_rows_per_launch(c_S, dims->S);
     return carve_fused(nullptr, dims->S, k, c_S).bytes;
 }
 
@@ -305,7 +309,7 @@ si_status si_indexer_topk_fused(const void* q, const void* K, const float* w, co
     if (!q || !K || !w || !out_idx || !out_score || !workspace) return SI_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return SI_ERR_INVALID_ARG;
     const si_dims d = *dims;
-    if (c_S < 1 || c_S > d.S) c_S = d.S;
+    c_S = fused_rows_per_launch(c_S, d.S);
     const FusedLayout L = carve_fused(workspace, d.S, k, c_S);
     if (L.bytes > workspace_bytes) return SI_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t hs = static_cast<hipStream_t>(stream);

@@ -50,6 +50,11 @@ constexpr int kQueriesPerBlock = 8;  // score kernel: one query per wave, 8 wave
 constexpr int kFusedMaxK = 1024;
 constexpr int kFusedTriggerMul = 2;
 constexpr int kFusedSlots = 256;
+// Queries per launch when the caller does not say: the workgroups of a launch drift apart as they
+// work through their items (and then miss each other's key rows in L2); a launch boundary brings
+// them back in step.  131072 rows cost no time against a single launch and cut the key traffic
+// to a third.
+constexpr int kFusedDefaultRows = 131072;
 
 // Per-row state of the current query tile, carved from the caller's workspace.
 struct RowBuffers {
