@@ -43,7 +43,7 @@ def main() -> int:
     ap.add_argument("--workload", default="flash_1m")
     ap.add_argument("--budget-gb", type=float, default=8.0, help="HBM budget for the workspace")
     ap.add_argument("--schedule", choices=["auto", "fused", "tiled"], default="auto",
-                    help="fused: single-pass kernel (k <= 1024); tiled: one launch per (c_S x c_T) "
+                    help="fused: single-pass kernel (k <= 2048); tiled: one launch per (c_S x c_T) "
                          "tile; auto: what si_indexer_topk picks (fused when it applies)")
     ap.add_argument("--c-s", type=int, default=0, help="explicit query tile (0 = planned)")
     ap.add_argument("--c-t", type=int, default=0, help="explicit key tile (0 = planned)")

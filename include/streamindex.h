@@ -87,7 +87,7 @@ si_status si_plan_tiles(const si_dims* dims, int32_t m, int32_t k, si_mask_mode 
 size_t si_workspace_bytes(const si_dims* dims, int32_t k, int32_t c_S, int32_t c_T);
 
 /* The whole step (Algorithm 2).  Runs the single-pass schedule (si_indexer_topk_fused, one
- * launch) when k <= 1024 and workspace_bytes >= si_fused_workspace_bytes(dims, k, 0); otherwise
+ * launches) when k <= 2048 and workspace_bytes >= si_fused_workspace_bytes(dims, k, 0); otherwise
  * the tiled schedule with the tiling si_plan_tiles chooses for budget = workspace_bytes.  Both
  * give the same bits.
  *   q         device [B,S,H_I,D] bf16        K  device [B,T,D] bf16      w  device [B,S,H_I] f32
@@ -111,7 +111,7 @@ si_status si_indexer_topk_tiled(const void* q, const void* K, const float* w,
  * cut back to its best k whenever it has collected 2k candidates) and writes out without
  * leaving the kernel.  No (c_S x c_T) candidate lists exist: the workspace holds one short row
  * buffer per resident wave plus one counter per launch, independent of S and T
- * (si_fused_workspace_bytes, about 40 MB at k = 1024).  Requires k <= 1024.
+ * (si_fused_workspace_bytes, about 40 MB at k = 1024).  Requires k <= 2048.
  * c_S = queries per kernel launch (<= 0: the library's default, 131072; values above S are
  * clamped).  The split only resynchronises the workgroups' walk over the keys; it does not
  * change the result. */

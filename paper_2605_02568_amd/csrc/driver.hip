@@ -280,7 +280,7 @@ si_status si_indexer_topk(const void* q, const void* K, const float* w, const si
                           int32_t m, int32_t k, si_mask_mode mask_mode, int32_t* out_idx,
                           float* out_score, void* workspace, size_t workspace_bytes,
                           void* stream) {
-    // The single-pass schedule whenever it applies (k <= 1024) and its small workspace fits;
+    // The single-pass schedule whenever it applies (k <= 2048) and its small workspace fits;
     // otherwise the tiled schedule with the plan for this budget.
     const size_t fused_bytes = si_fused_workspace_bytes(dims, k, 0);
     if (fused_bytes != 0 && fused_bytes <= workspace_bytes)

@@ -21,19 +21,21 @@ namespace si {
 // A sweep is stopped once a row holds `trigger` keys and can overshoot by 319 (see score_sweep).
 __host__ __device__ inline int fused_trigger(int k) { return kFusedTriggerMul * k; }
 __host__ __device__ inline int fused_row_cap(int k) { return fused_trigger(k) + 384; }
-constexpr int kFusedRegKeys = (kFusedTriggerMul * kFusedMaxK + 384 + 63) / 64;  // a whole row in registers
-constexpr int kFusedSortLds = kWaves * (kFusedMaxK + kFusedMaxK / 8) * 8;
-
-template <int D>
+// The kernel is compiled for two ranges of k (KMAX = 1024 and kFusedMaxK = 2048): a whole row
+// must fit the registers of a wave, and the sort area of the 8 waves must fit the LDS.
+template <int KMAX>
+constexpr int fused_reg_keys() { return (kFusedTriggerMul * KMAX + 384 + 63) / 64; }
+template <int D, int KMAX>
 constexpr int fused_lds_bytes() {
-    return sweep_lds_bytes<D>() > kFusedSortLds ? sweep_lds_bytes<D>() : kFusedSortLds;
+    constexpr int sort_bytes = kWaves * (KMAX + KMAX / 8) * 8;
+    return sweep_lds_bytes<D>() > sort_bytes ? sweep_lds_bytes<D>() : sort_bytes;
 }
 
 // Queries [s_begin, s_begin + rows) of every batch; work item = (batch, group of 8 queries),
 // handed out through *counter (zero before the launch), longest key range first so that the
 // workgroups running at any time have nearly equal work and walk the keys roughly together
 // (which keeps the key rows they share in L2).  Workgroup j uses rows [8j, 8j+8) of `slots`.
-template <int D, int HB>
+template <int D, int HB, int KMAX>
 __global__ __launch_bounds__(kScoreThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ K,
                           const float* __restrict__ w, int B, int S, int H, int T, int m,
@@ -43,7 +45,7 @@ void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
     // One LDS object for everything (sweep buffers / sort area, histograms, flags, work item):
     // with several, the compiler orders every LDS read behind the global -> LDS transfers in
     // flight and the key prefetch of the sweep no longer overlaps anything.
-    constexpr int kHistOff = fused_lds_bytes<D>();
+    constexpr int kHistOff = fused_lds_bytes<D, KMAX>();
     constexpr int kFlagsOff = kHistOff + kWaves * 256 * 4;
     constexpr int kItemOff = kFlagsOff + 2 * kWaves * 4;
     __shared__ __attribute__((aligned(1024))) unsigned char lds[kItemOff + 16];
@@ -106,7 +108,7 @@ void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
             // holds more than it would keep is cut back now, which also refreshes its threshold.
             if (threadIdx.x < 2 * kWaves) s_flags[threadIdx.x] = 0;
             if (o.n_cand > limit) {
-                RegKeys<kFusedRegKeys> keys;
+                RegKeys<fused_reg_keys<KMAX>()> keys;
                 keys.load(cand, o.n_cand);
                 int kept = 0;
                 const key64_t thr = wave_radix_kth(keys, k, limit, s_hist[wave], &kept);
@@ -126,7 +128,7 @@ void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
             const int n = o.n_cand;
             const int c = min(n, k);
             {
-                RegKeys<kFusedRegKeys> keys;
+                RegKeys<fused_reg_keys<KMAX>()> keys;
                 keys.load(cand, n);
                 key64_t thr = 0ull;
                 int kept = 0;
@@ -178,15 +180,20 @@ hipError_t launch_fused(const void* q, const void* K, const float* w, const si_d
     int pow2_k = 16;
     while (pow2_k < k) pow2_k <<= 1;
 #define SI_LAUNCH(DD, HH)                                                                          \
-    hipLaunchKernelGGL((indexer_fused_kernel<DD, HH>), grid, block, 0, stream, qp, Kp, w, d.B, d.S, \
-                       d.H_I, d.T, m, mask_mode, k, pow2_k, s_begin, rows, slots, counter, out_idx, \
-                       out_score)
-    if (d.D == 128 && HB == 2) SI_LAUNCH(128, 2);
-    else if (d.D == 128 && HB == 1) SI_LAUNCH(128, 1);
-    else if (d.D == 64 && HB == 2) SI_LAUNCH(64, 2);
-    else if (d.D == 64 && HB == 1) SI_LAUNCH(64, 1);
-    else if (d.D == 32 && HB == 2) SI_LAUNCH(32, 2);
-    else if (d.D == 32 && HB == 1) SI_LAUNCH(32, 1);
+    if (k <= 1024)                                                                                  \
+        hipLaunchKernelGGL((indexer_fused_kernel<DD, HH, 1024>), grid, block, 0, stream, qp, Kp, w, \
+                           d.B, d.S, d.H_I, d.T, m, mask_mode, k, pow2_k, s_begin, rows, slots,     \
+                           counter, out_idx, out_score);                                            \
+    else                                                                                            \
+        hipLaunchKernelGGL((indexer_fused_kernel<DD, HH, kFusedMaxK>), grid, block, 0, stream, qp,  \
+                           Kp, w, d.B, d.S, d.H_I, d.T, m, mask_mode, k, pow2_k, s_begin, rows,     \
+                           slots, counter, out_idx, out_score)
+    if (d.D == 128 && HB == 2) { SI_LAUNCH(128, 2); }
+    else if (d.D == 128 && HB == 1) { SI_LAUNCH(128, 1); }
+    else if (d.D == 64 && HB == 2) { SI_LAUNCH(64, 2); }
+    else if (d.D == 64 && HB == 1) { SI_LAUNCH(64, 1); }
+    else if (d.D == 32 && HB == 2) { SI_LAUNCH(32, 2); }
+    else if (d.D == 32 && HB == 1) { SI_LAUNCH(32, 1); }
     else return hipErrorInvalidValue;
 #undef SI_LAUNCH
     return hipGetLastError();

@@ -44,10 +44,10 @@ constexpr int kMaxK = 4096;
 constexpr int kMaxHeads = 64;
 constexpr int kQueriesPerBlock = 8;  // score kernel: one query per wave, 8 waves
 
-// Single-pass schedule (fused.hip): k up to kFusedMaxK; a row is merged once it holds
+// Single-pass schedule (fused.hip): k up to kFusedMaxK (a row must fit a wave's registers); a row is merged once it holds
 // kFusedTriggerMul * k keys; at most kFusedSlots workgroups are resident (one per compute unit
 // of an MI355X), each with 8 row buffers.
-constexpr int kFusedMaxK = 1024;
+constexpr int kFusedMaxK = 2048;
 constexpr int kFusedTriggerMul = 2;
 constexpr int kFusedSlots = 256;
 // Queries per launch when the caller does not say: the workgroups of a launch drift apart as they

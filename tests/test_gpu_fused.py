@@ -47,7 +47,9 @@ def _same(a, b):
     (1, 37, 33, 64, 200, 1, 7, 0, 0),        # ragged group, two head blocks, no mask
     (2, 203, 64, 128, 50, 4, 16, 1, 64),     # batch 2, ragged S, several launches
     (1, 2048, 64, 128, 512, 4, 64, 1, 0),    # V4 head shape: rows merge several times
-    (1, 1500, 64, 128, 3000, 1, 1024, 1, 0), # largest k; rows collect > 2k candidates
+    (1, 1500, 64, 128, 3000, 1, 1024, 1, 0), # k = 1024; rows collect > 2k candidates
+    (1, 1100, 64, 128, 5000, 1, 2048, 1, 0), # largest k of the single-pass schedule
+    (1, 600, 16, 32, 9000, 1, 1025, 0, 0),   # first k above 1024, long rows
     (1, 640, 8, 32, 5000, 1, 1, 0, 256),     # k = 1
     (3, 64, 31, 64, 900, 2, 100, 0, 0),      # k above and below the row lengths
 ])

@@ -59,7 +59,7 @@ def _run(wl, q, K, w, c_S, c_T, budget=None):
 
 
 def _run_default(wl, q, K, w, nbytes):
-    """si_indexer_topk with a workspace of nbytes: the single-pass schedule for k <= 1024."""
+    """si_indexer_topk with a workspace of nbytes: the single-pass schedule (k <= 2048)."""
     out_idx = torch.empty((wl.B, wl.S, wl.k), dtype=torch.int32, device=DEV)
     out_score = torch.empty((wl.B, wl.S, wl.k), dtype=torch.float32, device=DEV)
     ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
