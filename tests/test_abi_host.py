@@ -102,6 +102,34 @@ def test_null_pointers_and_small_workspace_rejected():
     assert lib.si_profile_read(None, None) == P.SI_ERR_INVALID_ARG
 
 
+def test_single_pass_workspace_and_argument_checks():
+    dims = (1, 1 << 20, 64, 128, 1 << 18)
+    # 256 resident workgroups x 8 rows x (2k + 384) keys, plus one counter per launch
+    ws = P.si_fused_workspace_bytes(*dims, 1024)
+    expect = 256 * 8 * (2 * 1024 + 384) * 8
+    assert expect <= ws <= expect + 2 * 256
+    # independent of the problem size, growing with k only
+    assert abs(P.si_fused_workspace_bytes(1, 4096, 64, 128, 1024, 1024) - ws) <= 256
+    assert P.si_fused_workspace_bytes(*dims, 2048) > ws > P.si_fused_workspace_bytes(*dims, 64)
+    assert P.si_fused_workspace_bytes(*dims, 2049) == 0 and P.si_fused_workspace_bytes(*dims, 0) == 0
+    # more launches, more counters
+    assert P.si_fused_workspace_bytes(*dims, 1024, 8) >= ws
+    lib = P.load()
+    d = binding.si_dims(1, 64, 4, 32, 16)
+    fake = ctypes.c_void_p(256)
+    call = lambda k, ws_bytes, q=fake, wsp=fake: lib.si_indexer_topk_fused(  # noqa: E731
+        q, fake, fake, ctypes.byref(d), 4, k, 1, 0, fake, fake, wsp, ws_bytes, None)
+    assert call(2049, 1 << 30) == P.SI_ERR_UNSUPPORTED_SHAPE
+    assert call(8, 16) == P.SI_ERR_WORKSPACE_TOO_SMALL
+    assert call(8, 1 << 30, q=None) == P.SI_ERR_INVALID_ARG
+    assert call(8, 1 << 30, wsp=ctypes.c_void_p(264)) == P.SI_ERR_INVALID_ARG
+    # si_indexer_topk falls back to the tiled plan when the single-pass workspace does not fit
+    small = P.si_workspace_bytes(1, 64, 4, 32, 16, 8, 8, 16)
+    assert small < P.si_fused_workspace_bytes(1, 64, 4, 32, 16, 8)
+    assert lib.si_indexer_topk(None, fake, fake, ctypes.byref(d), 4, 8, 1, fake, fake, fake, small,
+                               None) == P.SI_ERR_INVALID_ARG
+
+
 def test_product_package_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2605_02568_amd")
     for dirpath, _, files in os.walk(pkg):

@@ -88,3 +88,41 @@ def test_fused_adversarial_ascending_scores(oracle):
         np.zeros(S, dtype=np.int32), np.arange(S, dtype=np.int64), m, k, 0,
         fused[0].cpu().numpy().reshape(S, k), fused[1].cpu().numpy().reshape(S, k))
     assert stats["mean_recall"] > 0.999, stats
+
+
+def test_default_entry_point_falls_back_to_the_tiled_plan():
+    """si_indexer_topk with a workspace too small for the single-pass schedule plans tiles for
+    that budget instead, and with k above 2048 it always does; same bits either way."""
+    B, S, H, D, T, m, k = 1, 512, 64, 128, 128, 4, 32
+    q, K, w = _rand_problem(5, B, S, H, D, T)
+    qd, Kd, wd = q.to(DEV), K.to(DEV), w.to(DEV)
+    fused = _run("fused", qd, Kd, wd, m, k, 1, 0)
+    small = P.si_workspace_bytes(B, S, H, D, T, k, 64, 64)
+    assert small < P.si_fused_workspace_bytes(B, S, H, D, T, k)
+    out_idx = torch.empty_like(fused[0])
+    out_score = torch.empty_like(fused[1])
+    ws = torch.empty(small, dtype=torch.uint8, device=DEV)
+    P.si_profile_reset()
+    P.si_profile_enable(True)
+    P.si_indexer_topk(qd, Kd, wd, m, k, 1, out_idx, out_score, ws)
+    torch.cuda.synchronize()
+    prof = P.si_profile_read()
+    P.si_profile_enable(False)
+    assert prof["fused"][1] == 0 and prof["score_tile"][1] > 0
+    assert _same((out_idx, out_score), fused)
+    # k = 4096: beyond the single-pass schedule
+    k2 = 4096
+    big = torch.empty(64 << 20, dtype=torch.uint8, device=DEV)
+    oi = torch.empty((B, S, k2), dtype=torch.int32, device=DEV)
+    os_ = torch.empty((B, S, k2), dtype=torch.float32, device=DEV)
+    P.si_profile_reset()
+    P.si_profile_enable(True)
+    P.si_indexer_topk(qd, Kd, wd, m, k2, 1, oi, os_, big)
+    torch.cuda.synchronize()
+    prof = P.si_profile_read()
+    P.si_profile_enable(False)
+    assert prof["fused"][1] == 0 and prof["score_tile"][1] > 0
+    assert torch.equal(oi[:, :, :k], fused[0][:, :, :k].where(fused[0][:, :, :k] >= 0, oi[:, :, :k]))
+    valid = (oi[0] >= 0).sum(dim=1).cpu().numpy()
+    t = np.arange(S)
+    assert np.array_equal(valid, np.minimum(k2, np.minimum(T, (t + 1) // m)))
