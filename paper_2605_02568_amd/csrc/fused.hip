@@ -47,7 +47,7 @@ void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
     // flight and the key prefetch of the sweep no longer overlaps anything.
     constexpr int kHistOff = fused_lds_bytes<D, KMAX>();
     constexpr int kFlagsOff = kHistOff + kWaves * 256 * 4;
-    constexpr int kItemOff = kFlagsOff + 2 * kWaves * 4;
+    constexpr int kItemOff = kFlagsOff + 2 * 4;
     __shared__ __attribute__((aligned(1024))) unsigned char lds[kItemOff + 16];
     int (*s_hist)[256] = reinterpret_cast<int (*)[256]>(lds + kHistOff);
     int* s_flags = reinterpret_cast<int*>(lds + kFlagsOff);
@@ -63,7 +63,7 @@ void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
 
     for (;;) {
         if (threadIdx.x == 0) s_item = atomicAdd(counter, 1);
-        if (threadIdx.x < 2 * kWaves) s_flags[threadIdx.x] = 0;
+        if (threadIdx.x < 2) s_flags[threadIdx.x] = 0;
         __syncthreads();
         const int item = s_item;
         __syncthreads();  // everybody has read s_item before the next round overwrites it
@@ -106,7 +106,7 @@ void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
             if (kbeg >= group_keys) break;
             // Merge: the sweep stopped because some row reached the trigger.  Every row that
             // holds more than it would keep is cut back now, which also refreshes its threshold.
-            if (threadIdx.x < 2 * kWaves) s_flags[threadIdx.x] = 0;
+            if (threadIdx.x < 2) s_flags[threadIdx.x] = 0;
             if (o.n_cand > limit) {
                 RegKeys<fused_reg_keys<KMAX>()> keys;
                 keys.load(cand, o.n_cand);

@@ -106,10 +106,11 @@ struct SweepOut {
 // with the same Kb, key_clamp and n_keys > 0.
 //
 // STOPPABLE (filter mode): the sweep also ends, for the whole workgroup at the same key, once
-// some wave holds at least `trigger` keys.  Each wave posts that condition in `flags`
-// (LDS, [2][kWaves] ints, zero on entry) after a 128-key step, and everybody reads the flags
-// of the previous step behind the step's barrier, so the decision is uniform without another
-// barrier.  A row can therefore grow to at most trigger + 319 keys before the sweep returns.
+// some wave holds at least `trigger` keys.  Such a wave sets flags[step parity] (LDS, 2 ints,
+// zero on entry) after its 128-key step, and everybody reads the word of the previous step behind
+// the step's barrier, so the decision is uniform without another barrier and nothing has to be
+// cleared on the way.  A row can therefore grow to at most trigger + 319 keys before the sweep
+// returns.
 //
 // Returns the number of keys swept (a multiple of 128, or >= n_keys at the natural end).  On
 // return every global -> LDS transfer the workgroup issued has landed for the calling wave;
@@ -248,11 +249,7 @@ __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         int posted = 0;
-        if (STOPPABLE) {  // what the waves posted after the previous step
-            const int* f = flags + (((kc0 / kKeyChunk) + 1) & 1) * kWaves;
-#pragma unroll
-            for (int i = 0; i < kWaves; ++i) posted |= f[i];
-        }
+        if (STOPPABLE) posted = flags[((kc0 / kKeyChunk) + 1) & 1];  // posted after the previous step
         SI_STEP(accB, accA, s2v, off_next)
         // even sub-blocks stay in the low half-wave, odd ones in the high half
         const float res_prev = half ? sp : r_even;   // keys kc0 - 64 + lane (previous chunk)
@@ -263,7 +260,9 @@ __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)
             SI_EMIT(res_cur, kc0)
         }
         if (STOPPABLE) {
-            if (lane == 0) flags[((kc0 / kKeyChunk) & 1) * kWaves + wave] = n_cand >= trigger ? 1 : 0;
+            if (n_cand >= trigger) {  // wave-uniform, rare
+                if (lane == 0) flags[(kc0 / kKeyChunk) & 1] = 1;
+            }
             stop = __builtin_amdgcn_readfirstlane(posted) != 0;
         }
         const int t_ = off_cur; off_cur = off_next; off_next = off_nn; off_nn = t_;
