@@ -48,7 +48,7 @@ extern "C" {
 typedef enum {
     SI_OK = 0,
     SI_ERR_INVALID_ARG = -1,        /* null pointer, non-positive size, bad enum               */
-    SI_ERR_UNSUPPORTED_SHAPE = -2,  /* D not in {32,64,128}, H_I > 64, k > 4096, T >= 2^31     */
+    SI_ERR_UNSUPPORTED_SHAPE = -2,  /* D not in {32,64,128}, H_I > 64, k > 4096, T*D*2 >= 2^32 */
     SI_ERR_WORKSPACE_TOO_SMALL = -3,
     SI_ERR_HIP = -4                 /* a HIP runtime call failed; see si_last_hip_error()      */
 } si_status;

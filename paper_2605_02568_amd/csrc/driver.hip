@@ -92,6 +92,8 @@ si_status check_dims(const si_dims* d, int32_t m, int32_t k, int mask_mode) {
     if (mask_mode != SI_MASK_NONE && mask_mode != SI_MASK_CAUSAL_BLOCK) return SI_ERR_INVALID_ARG;
     if (d->D != 32 && d->D != 64 && d->D != 128) return SI_ERR_UNSUPPORTED_SHAPE;
     if (d->H_I > kMaxHeads || k > kMaxK) return SI_ERR_UNSUPPORTED_SHAPE;
+    // the score sweep addresses one batch's keys through a 32-bit buffer range
+    if (static_cast<int64_t>(d->T) * d->D * 2 >= (int64_t{1} << 32)) return SI_ERR_UNSUPPORTED_SHAPE;
     return SI_OK;
 }
 
@@ -392,7 +394,7 @@ const char* si_strerror(si_status status) {
     switch (status) {
         case SI_OK: return "ok";
         case SI_ERR_INVALID_ARG: return "invalid argument";
-        case SI_ERR_UNSUPPORTED_SHAPE: return "unsupported shape (D in {32,64,128}, H_I <= 64, k <= 4096)";
+        case SI_ERR_UNSUPPORTED_SHAPE: return "unsupported shape (D in {32,64,128}, H_I <= 64, k <= 4096, T*D*2 < 2^32)";
         case SI_ERR_WORKSPACE_TOO_SMALL: return "workspace too small for this tiling";
         case SI_ERR_HIP: return "HIP runtime error (see si_last_hip_error)";
     }

@@ -101,8 +101,8 @@ struct SweepOut {
     float* out_row;    // fp32 scores of the sweep's keys
 };
 
-// Sweeps keys [0, n_keys) of Kb (a multiple of 128 is covered: key rows past `key_clamp - 1`
-// repeat that row and are never emitted).  All 8 waves of the workgroup must call it together
+// Sweeps keys [0, n_keys) of Kb (a multiple of 128 is covered: key rows from `key_clamp` on read
+// as zero and are never emitted; key_clamp * 2D < 2^32).  All 8 waves of the workgroup must call it together
 // with the same Kb, key_clamp and n_keys > 0.
 //
 // STOPPABLE (filter mode): the sweep also ends, for the whole workgroup at the same key, once
@@ -120,6 +120,7 @@ __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)
                                            const float (&wr)[HB][16], const __bf16* __restrict__ Kb,
                                            int key_clamp, int n_keys, SweepOut& o, int* flags,
                                            int trigger) {
+#if defined(__HIP_DEVICE_COMPILE__)
     static_assert(!STOPPABLE || FILTER, "only the filtering sweep can be stopped");
     constexpr int KS = D / 16;             // MFMA steps along d
     constexpr int EPM = 16 / KS;           // epilogue elements handled next to one MFMA
@@ -152,26 +153,38 @@ __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)
 
     // Global -> LDS without a register round trip: each wave-wide load writes 1 KiB of LDS
     // (lane l to byte l*16 of the block); the lane picks the global piece that belongs there.
+    // Buffer addressing: the lane's part of the address (key row inside the chunk, piece) is a
+    // constant 32-bit offset, the chunk's part a scalar, and key rows past the end of the sweep's
+    // key range read as zero (they are never emitted), so a load costs no vector ALU work.
     typedef __attribute__((address_space(3))) void lds_void;
-    typedef __attribute__((address_space(1))) const void gbl_void;
-#define SI_FETCH(KC0, BUFOFF)                                                                      \
-    _Pragma("unroll") for (int i = 0; i < kLoads; ++i) {                                            \
-        const int blk = wave * kLoads + i;                   /* 1 KiB block inside the chunk */     \
-        const int row = blk * kRowsPerLoad + lane / kPieces; /* key row inside the chunk */         \
-        const int piece = (lane % kPieces) ^ ((row / kRowsPer256) % kPieces);                       \
-        const int key = min((KC0) + row, key_clamp - 1); /* rows past the edge repeat the last key */ \
-        const __bf16* src = Kb + static_cast<int64_t>(key) * D + piece * 8;                         \
-        __builtin_amdgcn_global_load_lds((gbl_void*)(src),                                          \
-            (lds_void*)(lds + (BUFOFF) + blk * 1024), 16, 0, 0);                                    \
+    // (descriptor: raw buffer, stride 0, num_records = bytes of the key range, untyped 32-bit data;
+    // the host checks that a batch's keys stay below 4 GiB)
+    const __amdgpu_buffer_rsrc_t krsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<__bf16*>(Kb), 0,
+        static_cast<int>(static_cast<unsigned>(key_clamp) * static_cast<unsigned>(kRowBytes)), 0x00020000);
+    int kvoff[kLoads];
+#pragma unroll
+    for (int i = 0; i < kLoads; ++i) {
+        const int blk = wave * kLoads + i;                   // 1 KiB block inside the chunk
+        const int row = blk * kRowsPerLoad + lane / kPieces; // key row inside the chunk
+        const int piece = (lane % kPieces) ^ ((row / kRowsPer256) % kPieces);
+        kvoff[i] = row * kRowBytes + piece * 16;
     }
+#define SI_FETCH(KC0, BUFOFF)                                                                      \
+    _Pragma("unroll") for (int i = 0; i < kLoads; ++i)                                              \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(krsrc,                                                 \
+            (lds_void*)(lds + (BUFOFF) + (wave * kLoads + i) * 1024), 16, kvoff[i],                 \
+            static_cast<int>(static_cast<unsigned>(KC0) * static_cast<unsigned>(kRowBytes)), 0, 0);
 
     // This lane's byte offset, inside a 32-key sub-block, of the operand for MFMA step ks.
     const int swz = (col / kRowsPer256) % kPieces;
-    int koff[KS];
+    // kaddr[ks] is kept absolute (buffer offset included) and moved from buffer to buffer once per
+    // chunk, so that the sub-block and MFMA-step parts of a read's address are immediates.
+    int kaddr[KS];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) koff[ks] = col * kRowBytes + (((ks * 2 + half) ^ swz) * 16);
-#define SI_KREAD(BYTEOFF, KSTEP) \
-    (*reinterpret_cast<const bf16x8*>(lds + (BYTEOFF) + koff[KSTEP]))
+    for (int ks = 0; ks < KS; ++ks) kaddr[ks] = col * kRowBytes + (((ks * 2 + half) ^ swz) * 16);
+#define SI_KREAD(SUBBLOCK, KSTEP) \
+    (*reinterpret_cast<const bf16x8*>(lds + kaddr[KSTEP] + (SUBBLOCK) * 32 * kRowBytes))
 
     // Chunks 0 and 1 in flight; chunk 0 must have landed before its first read.
     int off_cur = 0, off_next = kBufBytes, off_nn = 2 * kBufBytes;  // LDS buffers: being read, next, filling
@@ -182,7 +195,7 @@ __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)
 
     bf16x8 bq[KS];  // key operand of the sub-block about to be multiplied
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) bq[ks] = SI_KREAD(off_cur, ks);
+    for (int ks = 0; ks < KS; ++ks) bq[ks] = SI_KREAD(0, ks);  // kaddr points into buffer 0 = off_cur
 
     // Software pipeline, one step per 32-key sub-block: the MFMAs of sub-block g fill one
     // accumulator set while the ReLU / weight / head-sum epilogue drains the other one (sub-block
@@ -195,7 +208,7 @@ __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)
     const floatx16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
     for (int hb = 0; hb < HB; ++hb) accB[hb] = zero16;
-#define SI_STEP(CUR, PREV, OUT, NEXT_BYTEOFF)                                                      \
+#define SI_STEP(CUR, PREV, OUT, NEXT_SUBBLOCK)                                                      \
     {                                                                                               \
         float s_ = 0.0f;                                                                            \
         _Pragma("unroll") for (int hb = 0; hb < HB; ++hb)                                           \
@@ -204,7 +217,7 @@ __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)
                                                                   ks == 0 ? zero16 : CUR[hb], 0, 0, 0); \
                 _Pragma("unroll") for (int e = (hb * KS + ks) * EPM; e < (hb * KS + ks + 1) * EPM; ++e)   \
                     s_ = fmaf(wr[e / 16][e % 16], relu(PREV[e / 16][e % 16]), s_);                  \
-                if (hb == HB - 1) bq[ks] = SI_KREAD(NEXT_BYTEOFF, ks);                              \
+                if (hb == HB - 1) bq[ks] = SI_KREAD(NEXT_SUBBLOCK, ks);                             \
                 __builtin_amdgcn_sched_barrier(0);                                                  \
             }                                                                                       \
         OUT = s_ + __shfl_xor(s_, 32);                                                              \
@@ -235,9 +248,9 @@ __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)
         // the buffer is unused if the chunk does not exist) so that the vmcnt arithmetic below holds.
         SI_FETCH(kc0 + 2 * kKeyChunk, off_nn)
         float sp, s0v, s1v, s2v;
-        SI_STEP(accA, accB, sp, off_cur + 1 * 32 * kRowBytes)
-        SI_STEP(accB, accA, s0v, off_cur + 2 * 32 * kRowBytes)
-        SI_STEP(accA, accB, s1v, off_cur + 3 * 32 * kRowBytes)
+        SI_STEP(accA, accB, sp, 1)
+        SI_STEP(accB, accA, s0v, 2)
+        SI_STEP(accA, accB, s1v, 3)
         // The next chunk must be in LDS, and visible to every wave, before its first read below.
         // A bare barrier: __syncthreads() would add a release fence that waits for every vector
         // memory operation, i.e. also for the chunk that has just started its trip.  What the
@@ -250,7 +263,12 @@ __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)
         asm volatile("" ::: "memory");
         int posted = 0;
         if (STOPPABLE) posted = flags[((kc0 / kKeyChunk) + 1) & 1];  // posted after the previous step
-        SI_STEP(accB, accA, s2v, off_next)
+        {   // from here on the reads go to the next chunk's buffer
+            const int delta = off_next - off_cur;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) kaddr[ks] += delta;
+        }
+        SI_STEP(accB, accA, s2v, 0)
         // even sub-blocks stay in the low half-wave, odd ones in the high half
         const float res_prev = half ? sp : r_even;   // keys kc0 - 64 + lane (previous chunk)
         const float res_cur = half ? s1v : s0v;      // keys kc0 + lane
@@ -283,6 +301,10 @@ __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)
     // loads of chunks past the end may still be in flight: let them land before the LDS is reused
     __builtin_amdgcn_s_waitcnt(0x0F70);
     return kc0;
+#else  // the host pass only needs the declaration (the buffer intrinsics are device-only)
+    (void)lds; (void)a; (void)wr; (void)Kb; (void)key_clamp; (void)n_keys; (void)o; (void)flags; (void)trigger;
+    return 0;
+#endif
 }
 
 }  // namespace si

@@ -67,6 +67,7 @@ def test_plan_respects_budget_and_shapes():
     (dict(D=48), P.SI_ERR_UNSUPPORTED_SHAPE),
     (dict(H_I=65), P.SI_ERR_UNSUPPORTED_SHAPE),
     (dict(k=4097), P.SI_ERR_UNSUPPORTED_SHAPE),
+    (dict(T=1 << 24, D=128), P.SI_ERR_UNSUPPORTED_SHAPE),  # one batch of keys must stay below 4 GiB
     (dict(k=0), P.SI_ERR_INVALID_ARG),
     (dict(m=0), P.SI_ERR_INVALID_ARG),
     (dict(S=0), P.SI_ERR_INVALID_ARG),
