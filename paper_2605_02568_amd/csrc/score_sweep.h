@@ -142,12 +142,15 @@ __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)
     const int lane = threadIdx.x & 63;
     const int col = lane & 31;
     const int half = lane >> 5;
-    const int row_keys = o.row_keys;
-    const float theta = o.theta;
-    key64_t* const cand = o.cand;
-    const int cap = o.cap;
-    int n_cand = o.n_cand;
-    const uint32_t index0 = o.index0;
+    // Row state is wave-uniform; readfirstlane tells the compiler so (the merge computes the count
+    // and the threshold with cross-lane operations, which it would otherwise treat as per-lane
+    // values: vector registers, exec-masked branches).
+    const int row_keys = __builtin_amdgcn_readfirstlane(o.row_keys);
+    const float theta = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(o.theta)));
+    key64_t* const cand = o.cand;  // computed from the workgroup and wave numbers: uniform
+    const int cap = __builtin_amdgcn_readfirstlane(o.cap);
+    int n_cand = __builtin_amdgcn_readfirstlane(o.n_cand);
+    const uint32_t index0 = __builtin_amdgcn_readfirstlane(o.index0);
     const bool live = o.live;
     float* const out_row = o.out_row;
 
@@ -225,18 +228,27 @@ __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)
     // 64 finished scores (lane l holds key KEY0 + l): append the kept ones / store them.
 #define SI_EMIT(VAL, KEY0)                                                                         \
     {                                                                                               \
-        const int key = (KEY0) + lane;                                                              \
         if (FILTER) {                                                                               \
-            const bool keep = key >= 0 && key < row_keys && (VAL) > theta;                          \
-            const unsigned long long mask = __ballot(keep);                                         \
-            if (mask != 0ull && n_cand + static_cast<int>(__popcll(mask)) <= cap) { /* always, see SweepOut */ \
-                const int below = __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(mask >> 32),      \
-                                  __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(mask), 0u));      \
-                if (keep) cand[n_cand + below] = make_key((VAL), index0 + static_cast<uint32_t>(key)); \
-                n_cand += __popcll(mask);                                                           \
+            /* KEY0 is wave-uniform and negative only in the first step of a sweep */               \
+            if ((KEY0) >= 0) {                                                                      \
+                const bool legal = lane < row_keys - (KEY0);                                        \
+                const bool above = (VAL) > theta;                                                   \
+                const unsigned long long mask =                                                     \
+                    __builtin_amdgcn_ballot_w64(legal) & __builtin_amdgcn_ballot_w64(above);        \
+                const int add = static_cast<int>(__popcll(mask));                                   \
+                if (add != 0 && n_cand + add <= cap) { /* the second test always holds, see SweepOut */ \
+                    const unsigned below = __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(mask >> 32), \
+                                           __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(mask), 0u)); \
+                    const unsigned byte_off = (static_cast<unsigned>(n_cand) + below) * 8u;         \
+                    if (legal && above)                                                             \
+                        *reinterpret_cast<key64_t*>(reinterpret_cast<char*>(cand) + byte_off) =     \
+                            make_key((VAL), index0 + static_cast<uint32_t>((KEY0) + lane));         \
+                    n_cand += add;                                                                  \
+                }                                                                                   \
             }                                                                                       \
-        } else if (live && key >= 0 && key < n_keys) {                                              \
-            out_row[key] = (VAL);                                                                   \
+        } else {                                                                                    \
+            const int key = (KEY0) + lane;                                                          \
+            if (live && key >= 0 && key < n_keys) out_row[key] = (VAL);                             \
         }                                                                                           \
     }
 
@@ -273,7 +285,7 @@ __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)
         const float res_prev = half ? sp : r_even;   // keys kc0 - 64 + lane (previous chunk)
         const float res_cur = half ? s1v : s0v;      // keys kc0 + lane
         r_even = s2v;
-        if (!FILTER || __ballot((res_prev > theta) | (res_cur > theta)) != 0ull) {
+        if (!FILTER || __builtin_amdgcn_ballot_w64((res_prev > theta) | (res_cur > theta)) != 0ull) {
             SI_EMIT(res_prev, kc0 - 64)
             SI_EMIT(res_cur, kc0)
         }
