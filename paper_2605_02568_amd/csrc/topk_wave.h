@@ -200,44 +200,46 @@ __device__ inline void sort_pass(key64_t* s, int P, int b, int size) {
     __builtin_amdgcn_wave_barrier();
 }
 
-// The four lowest strides (8, 4, 2, 1) on a lane's own block of 16 consecutive keys; with
-// FIRST, the whole network up to runs of 16 (sizes 2, 4, 8, 16) instead.
-template <bool FIRST>
-__device__ inline void sort_block16(key64_t* s, int P, int size) {
+// The LG lowest strides (2^(LG-1) .. 1) on a lane's own block of E = 2^LG consecutive keys (LG = 3
+// or 4, so that a block never straddles a padding gap); with FIRST, the whole network up to runs
+// of E (sizes 2 .. E) instead.
+template <int LG, bool FIRST>
+__device__ inline void sort_block(key64_t* s, int P, int size) {
+    constexpr int E = 1 << LG;
     typedef key64_t key64x2 __attribute__((ext_vector_type(2)));
     const SortSlot slot;
     const int lane = threadIdx.x & 63;
-    for (int base = 16 * lane; base < P; base += 16 * 64) {
+    for (int base = E * lane; base < P; base += E * 64) {
         key64x2* blk = reinterpret_cast<key64x2*>(s + slot(base));  // 16-byte aligned
-        key64_t v[16];
+        key64_t v[E];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < E / 2; ++j) {
             const key64x2 t = blk[j];
             v[2 * j] = t.x;
             v[2 * j + 1] = t.y;
         }
         if (FIRST) {
 #pragma unroll
-            for (int sz = 2; sz <= 16; sz <<= 1)
+            for (int sz = 2; sz <= E; sz <<= 1)
 #pragma unroll
                 for (int d = sz >> 1; d > 0; d >>= 1)
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) {
+                    for (int i = 0; i < E / 2; ++i) {
                         const int lo = 2 * i - (i & (d - 1));
                         compare_exchange(v[lo], v[lo + d], ((base + lo) & sz) == 0);
                     }
         } else {
             const bool descending = (base & size) == 0;
 #pragma unroll
-            for (int d = 8; d > 0; d >>= 1)
+            for (int d = E / 2; d > 0; d >>= 1)
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
+                for (int i = 0; i < E / 2; ++i) {
                     const int lo = 2 * i - (i & (d - 1));
                     compare_exchange(v[lo], v[lo + d], descending);
                 }
         }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < E / 2; ++j) {
             key64x2 t;
             t.x = v[2 * j];
             t.y = v[2 * j + 1];
@@ -247,13 +249,15 @@ __device__ inline void sort_block16(key64_t* s, int P, int size) {
     __builtin_amdgcn_wave_barrier();
 }
 
-// s: sort_slots(P) keys of LDS owned by this wave, key i at s[SortSlot()(i)].
-__device__ inline void wave_sort_descending(key64_t* s, int P) {
-    sort_block16<true>(s, P, 0);
-    for (int lg = 5; (1 << lg) <= P; ++lg) {
+// LG = keys per lane and pass (as a power of two): 4 keeps all 64 lanes busy from P = 1024 on,
+// 3 does so for P = 512.
+template <int LG>
+__device__ inline void wave_sort_descending_by(key64_t* s, int P) {
+    sort_block<LG, true>(s, P, 0);
+    for (int lg = LG + 1; (1 << lg) <= P; ++lg) {
         const int size = 1 << lg;
-        for (int top = lg; top > 4;) {  // stride bits [4, lg), four at a time from the top
-            const int nb = min(4, top - 4);
+        for (int top = lg; top > LG;) {  // stride bits [LG, lg), up to LG at a time from the top
+            const int nb = min(LG, top - LG);
             const int b = top - nb;
             if (nb == 4) sort_pass<4>(s, P, b, size);
             else if (nb == 3) sort_pass<3>(s, P, b, size);
@@ -261,8 +265,14 @@ __device__ inline void wave_sort_descending(key64_t* s, int P) {
             else sort_pass<1>(s, P, b, size);
             top = b;
         }
-        sort_block16<false>(s, P, size);
+        sort_block<LG, false>(s, P, size);
     }
+}
+
+// s: sort_slots(P) keys of LDS owned by this wave, key i at s[SortSlot()(i)]; P a power of two >= 16.
+__device__ inline void wave_sort_descending(key64_t* s, int P) {
+    if (P <= 512) wave_sort_descending_by<3>(s, P);
+    else wave_sort_descending_by<4>(s, P);
 }
 
 }  // namespace si
