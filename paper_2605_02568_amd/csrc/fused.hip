@@ -84,6 +84,10 @@ void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
         o.n_cand = 0;
         o.live = live;
         o.out_row = nullptr;
+        // the first two key chunks of every sweep start their trip before the query is (re)loaded,
+        // and, after a stop, before the merge
+        if (group_keys > 0)
+            sweep_prefetch<D>(lds, K + static_cast<int64_t>(b) * T * D, T);
         for (int kbeg = 0; kbeg < group_keys;) {
             {
                 bf16x8 a[HB][D / 16];
@@ -99,7 +103,7 @@ void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
                 o.row_keys = row_keys - kbeg;
                 o.index0 = static_cast<uint32_t>(kbeg);
                 const __bf16* Kb = K + (static_cast<int64_t>(b) * T + kbeg) * D;
-                kbeg += score_sweep<D, HB, true, true>(lds, a, wr, Kb, T - kbeg, group_keys - kbeg, o,
+                kbeg += score_sweep<D, HB, true, true, true>(lds, a, wr, Kb, T - kbeg, group_keys - kbeg, o,
                                                        s_flags, trigger);
             }
             __syncthreads();  // the sweep's LDS and flags are free again
@@ -107,6 +111,7 @@ void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
             // Merge: the sweep stopped because some row reached the trigger.  Every row that
             // holds more than it would keep is cut back now, which also refreshes its threshold.
             if (threadIdx.x < 2) s_flags[threadIdx.x] = 0;
+            sweep_prefetch<D>(lds, K + (static_cast<int64_t>(b) * T + kbeg) * D, T - kbeg);
             if (o.n_cand > limit) {
                 RegKeys<fused_reg_keys<KMAX>()> keys;
                 keys.load(cand, o.n_cand);

@@ -85,6 +85,41 @@ __device__ __forceinline__ void load_query(const __bf16* __restrict__ q, const f
     }
 }
 
+// Starts the trip of the first two 128-key chunks of a sweep over Kb into LDS buffers 0 and 1
+// (the same transfers the sweep's own prologue would issue).  A sweep called with
+// PREFETCHED = true expects them in flight or landed and skips its own.  All 8 waves call it.
+template <int D>
+__device__ __forceinline__ void sweep_prefetch(unsigned char* lds, const __bf16* __restrict__ Kb,
+                                               int key_clamp) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    constexpr int kRowBytes = D * 2;
+    constexpr int kPieces = D / 8;
+    constexpr int kRowsPer256 = 256 / kRowBytes;
+    constexpr int kBufBytes = kKeyChunk * kRowBytes;
+    constexpr int kRowsPerLoad = 64 / kPieces;
+    constexpr int kLoads = kKeyChunk / kRowsPerLoad / kWaves;
+    typedef __attribute__((address_space(3))) void lds_void;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const __amdgpu_buffer_rsrc_t krsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<__bf16*>(Kb), 0,
+        static_cast<int>(static_cast<unsigned>(key_clamp) * static_cast<unsigned>(kRowBytes)), 0x00020000);
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int i = 0; i < kLoads; ++i) {
+            const int blk = wave * kLoads + i;
+            const int row = blk * kRowsPerLoad + lane / kPieces;
+            const int piece = (lane % kPieces) ^ ((row / kRowsPer256) % kPieces);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                krsrc, (lds_void*)(lds + c * kBufBytes + blk * 1024), 16, row * kRowBytes + piece * 16,
+                c * kKeyChunk * kRowBytes, 0, 0);
+        }
+#else
+    (void)lds; (void)Kb; (void)key_clamp;
+#endif
+}
+
 // What the sweep does with the scores of this wave's query.
 struct SweepOut {
     // filter mode
@@ -115,7 +150,7 @@ struct SweepOut {
 // Returns the number of keys swept (a multiple of 128, or >= n_keys at the natural end).  On
 // return every global -> LDS transfer the workgroup issued has landed for the calling wave;
 // a workgroup barrier must follow before the LDS is reused.
-template <int D, int HB, bool FILTER, bool STOPPABLE>
+template <int D, int HB, bool FILTER, bool STOPPABLE, bool PREFETCHED = false>
 __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)[HB][D / 16],
                                            const float (&wr)[HB][16], const __bf16* __restrict__ Kb,
                                            int key_clamp, int n_keys, SweepOut& o, int* flags,
@@ -191,8 +226,10 @@ __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)
 
     // Chunks 0 and 1 in flight; chunk 0 must have landed before its first read.
     int off_cur = 0, off_next = kBufBytes, off_nn = 2 * kBufBytes;  // LDS buffers: being read, next, filling
-    SI_FETCH(0, off_cur)
-    SI_FETCH(kKeyChunk, off_next)
+    if (!PREFETCHED) {
+        SI_FETCH(0, off_cur)
+        SI_FETCH(kKeyChunk, off_next)
+    }
     __builtin_amdgcn_s_waitcnt(0x0F70 | kLoads);  // vmcnt(kLoads): everything but chunk 1 has landed
     __syncthreads();
 
