@@ -61,13 +61,17 @@ void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
     const int limit = compact_limit(k);
     key64_t* const cand = slots.keys + (static_cast<int64_t>(blockIdx.x) * kQB + wave) * slots.cap;
 
+    // Work items: the next one is requested from the counter while the current one is processed,
+    // so its round trip costs nothing.
+    if (threadIdx.x == 0) s_item = atomicAdd(counter, 1);
+    __syncthreads();
+    int item = s_item;
     for (;;) {
-        if (threadIdx.x == 0) s_item = atomicAdd(counter, 1);
-        if (threadIdx.x < 2) s_flags[threadIdx.x] = 0;
-        __syncthreads();
-        const int item = s_item;
-        __syncthreads();  // everybody has read s_item before the next round overwrites it
         if (item >= n_items) break;  // uniform: every wave of every workgroup ends here
+        int next_item = 0;
+        if (threadIdx.x == 0) next_item = atomicAdd(counter, 1);
+        // (the sweep's first barrier orders this before any read of the flags)
+        if (threadIdx.x < 2) s_flags[threadIdx.x] = 0;
         const int b = item % B;
         const int r_first = (n_groups - 1 - item / B) * kQB;
         const int r = r_first + wave;
@@ -157,7 +161,9 @@ void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
                 }
             }
         }
+        if (threadIdx.x == 0) s_item = next_item;
         __syncthreads();  // the next item's sweep overwrites the LDS the sort used
+        item = s_item;
     }
 }
 
