@@ -23,6 +23,8 @@ __host__ __device__ inline int fused_trigger(int k) { return kFusedTriggerMul * 
 __host__ __device__ inline int fused_row_cap(int k) { return fused_trigger(k) + 384; }
 // The kernel is compiled for two ranges of k (KMAX = 1024 and kFusedMaxK = 2048): a whole row
 // must fit the registers of a wave, and the sort area of the 8 waves must fit the LDS.
+constexpr int kWarmupMaxKeys = 8192;
+
 template <int KMAX>
 constexpr int fused_reg_keys() { return (kFusedTriggerMul * KMAX + 384 + 63) / 64; }
 template <int D, int KMAX>
@@ -48,10 +50,13 @@ void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
     constexpr int kHistOff = fused_lds_bytes<D, KMAX>();
     constexpr int kFlagsOff = kHistOff + kWaves * 256 * 4;
     constexpr int kItemOff = kFlagsOff + 2 * 4;
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[kItemOff + 16];
+    constexpr int kTouchOff = kItemOff + 8;  // 16-byte aligned; landing area of the query warm-up reads
+    constexpr int kTouchLoads = 2;           // per wave: 2 x 64 lanes x 8 waves = 1024 cache lines = 8 V4 queries
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[kTouchOff + kWaves * kTouchLoads * 256];
     int (*s_hist)[256] = reinterpret_cast<int (*)[256]>(lds + kHistOff);
     int* s_flags = reinterpret_cast<int*>(lds + kFlagsOff);
     int& s_item = *reinterpret_cast<int*>(lds + kItemOff);
+    int& s_next = *reinterpret_cast<int*>(lds + kItemOff + 4);
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
@@ -110,6 +115,7 @@ void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
                 kbeg += score_sweep<D, HB, true, true, true>(lds, a, wr, Kb, T - kbeg, group_keys - kbeg, o,
                                                        s_flags, trigger);
             }
+            if (threadIdx.x == 0) s_next = next_item;  // (arrived long ago) for the warm-up below
             __syncthreads();  // the sweep's LDS and flags are free again
             if (kbeg >= group_keys) break;
             // Merge: the sweep stopped because some row reached the trigger.  Every row that
@@ -143,6 +149,31 @@ void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
                 int kept = 0;
                 if (n > k) thr = wave_radix_kth(keys, k, k, s_hist[wave], &kept);  // limit k: exact
                 wave_keep(keys, thr, s_sort, pow2_k, slot);
+            }
+            // While this wave sorts, the next item's query rows start their trip from HBM to L2
+            // (one 4-byte read per 128-byte line, landing in an LDS area nobody reads), so that
+            // the query load at the start of the next item finds them there.  Only for short
+            // items, where that latency is a visible share of the item (6 % at S = 32768); for
+            // long ones the 128 KB per workgroup only compete with the key rows for L2.
+            if (group_keys > 0 && group_keys <= kWarmupMaxKeys) {
+                const int nx = s_next;
+                if (nx < n_items) {
+                    const int nr_first = (n_groups - 1 - nx / B) * kQB;
+                    const int nrows = min(kQB, rows - nr_first);
+                    const int64_t nqrow = static_cast<int64_t>(nx % B) * S + s_begin + nr_first;
+                    const char* src = reinterpret_cast<const char*>(q + nqrow * H * D);
+                    const int lines = (nrows * H * D * 2 + 127) / 128;
+                    typedef __attribute__((address_space(3))) void lds_void;
+                    typedef __attribute__((address_space(1))) const void gbl_void;
+#pragma unroll
+                    for (int j = 0; j < kTouchLoads; ++j) {
+                        const int line = (j * kWaves + wave) * 64 + lane;
+                        if (line < lines)
+                            __builtin_amdgcn_global_load_lds(
+                                (gbl_void*)(src + static_cast<int64_t>(line) * 128),
+                                (lds_void*)(lds + kTouchOff + (wave * kTouchLoads + j) * 256), 4, 0, 0);
+                    }
+                }
             }
             int P = 16;
             while (P < c) P <<= 1;
