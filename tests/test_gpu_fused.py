@@ -126,3 +126,45 @@ def test_default_entry_point_falls_back_to_the_tiled_plan():
     valid = (oi[0] >= 0).sum(dim=1).cpu().numpy()
     t = np.arange(S)
     assert np.array_equal(valid, np.minimum(k2, np.minimum(T, (t + 1) // m)))
+
+
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        cases.append(dict(
+            B=int(rng.integers(1, 3)), H=int(rng.choice([1, 8, 32, 33, 64])), D=int(rng.choice([32, 64, 128])),
+            S=int(rng.integers(1, 900)), T=int(rng.integers(1, 20000)), m=int(rng.choice([1, 2, 4, 16])),
+            k=int(rng.choice([1, 3, 16, 64, 100, 512, 777, 1024, 1025, 2048])), mask=int(rng.integers(0, 2)),
+            c_S=int(rng.choice([0, 8, 64, 500])), dist=int(rng.integers(0, 3)),
+            c_T=int(rng.choice([128, 1000, 4096])), cs2=int(rng.choice([64, 256])), seed=1000 + i))
+    return cases
+
+
+@pytest.mark.parametrize("c", _random_cases(24, 20260514), ids=lambda c: f"S{c['S']}T{c['T']}k{c['k']}d{c['dist']}")
+def test_fused_and_tiled_agree_on_random_shapes_and_score_patterns(c):
+    """Both schedules, bit for bit, on seeded shapes with three score patterns: iid, scores that
+    rise with the key index (nothing can be filtered: a merge after every k keys) and small
+    integers (many exact ties: the index half of the order decides)."""
+    print("fused/tiled", c, flush=True)
+    B, S, H, D, T = c["B"], c["S"], c["H"], c["D"], c["T"]
+    g = torch.Generator(device="cpu").manual_seed(c["seed"])
+    q = torch.randn((B, S, H, D), generator=g)
+    K = torch.randn((B, T, D), generator=g)
+    w = torch.randn((B, S, H), generator=g) / np.sqrt(H)
+    if c["dist"] == 1:
+        K = K.abs() * torch.linspace(0.5, 4.0, T)[None, :, None]
+        q, w = q.abs(), w.abs()
+    elif c["dist"] == 2:
+        K = torch.randint(-1, 2, (B, T, D), generator=g).float()
+        q = torch.randint(-1, 2, (B, S, H, D), generator=g).float()
+        w = torch.ones((B, S, H))
+    qd, Kd, wd = q.to(torch.bfloat16).to(DEV), K.to(torch.bfloat16).to(DEV), w.to(DEV)
+    fused = _run("fused", qd, Kd, wd, c["m"], c["k"], c["mask"], c["c_S"])
+    tiled = _run("tiled", qd, Kd, wd, c["m"], c["k"], c["mask"], min(S, c["cs2"]), min(T, c["c_T"]))
+    assert _same(fused, tiled)
+    # structure: valid slots first, as many as there are legal keys (up to k), then pads
+    valid = (fused[0] >= 0).sum(dim=2).cpu().numpy()
+    t = np.arange(S)
+    legal = np.full(S, T) if c["mask"] == 0 else np.minimum(T, (t + 1) // c["m"])
+    assert np.array_equal(valid, np.broadcast_to(np.minimum(c["k"], legal), (B, S)))
