@@ -115,12 +115,16 @@ def main() -> int:
     # timed region: exactly `steps` steps, per-kernel HIP events recorded on the same stream
     P.si_profile_reset()
     P.si_profile_enable(True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]  # per-step spread
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record(stream)
+    for i in range(args.steps):
         step()
+        marks[i + 1].record(stream)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    per_step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     prof = P.si_profile_read()
     P.si_profile_enable(False)
     peak_alloc = torch.cuda.max_memory_allocated() - base_alloc
@@ -152,6 +156,8 @@ def main() -> int:
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": sec_per_step * 1e3,
+        "ms_per_step_min": per_step_ms[0],
+        "ms_per_step_median": per_step_ms[len(per_step_ms) // 2],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -206,8 +212,15 @@ def main() -> int:
         ora = O.topk_rows(q_rows, w_rows, K_bits, b_of, rows, wl.m, wl.k, wl.mask_mode, n_threads=threads)
         cpu_s = time.perf_counter() - t1
         pairs = int(sum(wl.legal_count(int(t)) for t in rows))
+        one = min(8, len(rows))  # a few rows on one thread: the oracle's single-core rate
+        t2 = time.perf_counter()
+        O.topk_rows(q_rows[-one:], w_rows[-one:], K_bits, b_of[-one:], rows[-one:], wl.m, wl.k, wl.mask_mode,
+                    n_threads=1)
+        one_s = time.perf_counter() - t2
+        one_pairs = int(sum(wl.legal_count(int(t)) for t in rows[-one:]))
         result["cpu_baseline"] = {
             "value": pairs / cpu_s, "unit": "pairs/s", "cores": threads, "kind": "oracle",
+            "value_one_core": one_pairs / one_s,
             "sample": f"{len(rows)} seeded query rows of {wl.name} (incl. edge rows), "
                       f"{pairs} legal pairs, fp64, full sort per row, {cpu_s:.1f} s",
         }
