@@ -12,6 +12,10 @@
 // One wave owns one query row, as in the score sweep; the merge and the write-out are the
 // wave-level routines of topk_wave.h, so no step needs an atomic or a cross-wave exchange.
 // The only workgroup-wide decisions are "next work item" and "stop the sweep for a merge".
+// Latencies at the seams are overlapped where that is free: the next work item is requested
+// while the current one runs, the first two key chunks of every sweep are on their way before
+// the query is (re)loaded and before a merge starts, and short items pull the next item's query
+// rows into L2 while they sort.
 
 #include "score_sweep.h"
 #include "topk_wave.h"
@@ -21,10 +25,11 @@ namespace si {
 // A sweep is stopped once a row holds `trigger` keys and can overshoot by 319 (see score_sweep).
 __host__ __device__ inline int fused_trigger(int k) { return kFusedTriggerMul * k; }
 __host__ __device__ inline int fused_row_cap(int k) { return fused_trigger(k) + 384; }
-// The kernel is compiled for two ranges of k (KMAX = 1024 and kFusedMaxK = 2048): a whole row
-// must fit the registers of a wave, and the sort area of the 8 waves must fit the LDS.
+// Items with at most this many keys warm L2 with the next item's query rows while they sort.
 constexpr int kWarmupMaxKeys = 8192;
 
+// The kernel is compiled for two ranges of k (KMAX = 1024 and kFusedMaxK = 2048): a whole row
+// must fit the registers of a wave, and the sort area of the 8 waves must fit the LDS.
 template <int KMAX>
 constexpr int fused_reg_keys() { return (kFusedTriggerMul * KMAX + 384 + 63) / 64; }
 template <int D, int KMAX>
