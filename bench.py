@@ -20,19 +20,50 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, the published (rounded) figure
+MFMA_BF16_FLOP_PER_CLK_PER_CU = 4096  # 4 SIMDs x 1024
+NOMINAL_CLOCK_GHZ = 2.4
 
 
-def _traffic_from_profiles(kernel: str, workload: str):
-    """HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (two runs), if
-    a summary for this kernel and workload has been committed under profiles/; else None."""
+def _traffic_from_profiles(kernel: str, workload: str, source_sha: str):
+    """(bytes per launch, sha of the sources it was measured on) of the dominant kernel from the
+    rocprofv3 --pmc summary committed under profiles/ for this kernel and workload.  The figure
+    is returned only when it was measured on the sources this run was built from; otherwise
+    (None, that file's sha), so that a stale counter never rides along with a fresh timing."""
     path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_traffic.txt")
     if not os.path.exists(path):
-        return None
+        return None, None
+    traffic, sha = None, None
     for line in open(path):
         if line.startswith("traffic_bytes_per_launch"):
-            return float(line.split()[1])
-    return None
+            traffic = float(line.split()[1])
+        if line.startswith("kernel_source_sha16"):
+            sha = line.split()[1]
+    if sha != source_sha:
+        return None, sha
+    return traffic, sha
+
+
+def _phase_budget(P, words, steps, kernel_ms_per_step):
+    """Per-step time budget of the single-pass kernel from its phase clock: for each phase the
+    mean over workgroups (ms per step and share of the kernel time), the slowest workgroup, and
+    what is left of the kernel time after the mean workgroup's residency (launch ramp and tail)."""
+    names = P.PHASE_NAMES
+    rate_khz = P.si_wall_clock_khz() or 100000  # the constant clock of this GPU family runs at 100 MHz
+    used = words[words[:, names.index("launches")] > 0]
+    if len(used) == 0:
+        return {"error": "the instrumented kernel did not run (head shape or k outside its range)"}
+    to_ms = 1.0 / rate_khz / steps
+    out = {"wall_clock_khz": int(rate_khz), "workgroups": int(len(used)), "kernel_ms_per_step": kernel_ms_per_step}
+    for i, name in enumerate(names):
+        col = used[:, i].astype("float64")
+        if i <= names.index("resident"):
+            out[name] = {"mean_ms": float(col.mean() * to_ms), "max_ms": float(col.max() * to_ms),
+                         "share_of_kernel": float(col.mean() * to_ms / kernel_ms_per_step)}
+        else:
+            out[name] = {"mean": float(col.mean() / steps), "max": float(col.max() / steps)}
+    out["ramp_and_tail_ms"] = kernel_ms_per_step - out["resident"]["mean_ms"]
+    return out
 
 
 def main() -> int:
@@ -51,6 +82,9 @@ def main() -> int:
                     help="rows of the workload the CPU oracle is timed (and checked) on; 0 = skip")
     ap.add_argument("--seq-len", type=int, default=0, help="override S of the workload (T = S/m follows)")
     ap.add_argument("--topk", type=int, default=0, help="override k of the workload")
+    ap.add_argument("--phases", action="store_true",
+                    help="single-pass schedule, V4 head shape, k <= 1024: run the instrumented kernel "
+                         "and add its per-phase time budget to the JSON line")
     ap.add_argument("--calibration-mib", type=int, default=0,
                     help="also run one plain elementwise kernel reading and writing this many MiB "
                          "(a known-size reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -66,6 +100,7 @@ def main() -> int:
 
     import paper_2605_02568_amd as P
     import workloads as W
+    from paper_2605_02568_amd.build import source_hash
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -112,6 +147,16 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
 
+    props = torch.cuda.get_device_properties(0)
+    n_cu = int(props.multi_processor_count)
+    phase_words = None
+    if args.phases:
+        if not fused:
+            print("bench.py: --phases needs the single-pass schedule", file=sys.stderr)
+            return 2
+        phase_words = torch.zeros(max(n_cu, 256) * P.PHASE_WORDS, dtype=torch.int64, device=dev)
+        P.si_profile_phases(phase_words, max(n_cu, 256))
+
     # timed region: exactly `steps` steps, per-kernel HIP events recorded on the same stream
     P.si_profile_reset()
     P.si_profile_enable(True)
@@ -128,6 +173,11 @@ def main() -> int:
     prof = P.si_profile_read()
     P.si_profile_enable(False)
     peak_alloc = torch.cuda.max_memory_allocated() - base_alloc
+    phase_budget = None
+    if phase_words is not None:
+        P.si_profile_phases(None)
+        phase_budget = _phase_budget(P, phase_words.cpu().numpy().reshape(-1, P.PHASE_WORDS), args.steps,
+                                     prof["fused"][0] / args.steps)
 
     if args.calibration_mib > 0:
         src = torch.ones(args.calibration_mib << 18, dtype=torch.float32, device=dev)
@@ -148,6 +198,9 @@ def main() -> int:
     flop_per_launch = flop_per_step * args.steps / max(1, score_launches)
     achieved = flop_per_launch / (score_ms_per_launch * 1e-3) / 1e12 if score_ms > 0 else 0.0
 
+    src_sha = source_hash()
+    traffic, traffic_sha = _traffic_from_profiles("indexer_fused" if fused else "score_tile", wl.name, src_sha)
+    peak_units = n_cu * MFMA_BF16_FLOP_PER_CLK_PER_CU * NOMINAL_CLOCK_GHZ * 1e9 / 1e12
     result = {
         "metric": "indexer q.key pairs scored+top-k per second (legal pairs)",
         "value": legal_pairs / sec_per_step,
@@ -188,13 +241,23 @@ def main() -> int:
             "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s",
             "frac": achieved / PEAK_BF16_TFLOPS,
-            "traffic": _traffic_from_profiles("indexer_fused" if fused else "score_tile", wl.name),
+            "traffic": traffic,
+            "traffic_measured_on_sources": traffic_sha,
             "flop_per_launch": flop_per_launch,
             "ms_per_launch": score_ms_per_launch,
+            # the same fraction against the peak derived from this device's unit count:
+            # compute units x 4096 bf16 FLOP/clk x 2.4 GHz
+            "compute_units": n_cu,
+            "peak_from_units": peak_units,
+            "frac_of_peak_from_units": achieved / peak_units,
         },
+        "kernel_source_sha16": src_sha,
         "paper_context": "single NVIDIA H200: materialize OOM at S=65,536; StreamIndex S=1,048,576 "
                          "in 30.9 s at 6.21 GB peak HBM (Table 2)",
     }
+
+    if phase_budget is not None:
+        result["phase_budget"] = phase_budget
 
     if args.oracle_rows > 0:
         from oracle import oracle as O  # cpu_baseline leg only
@@ -227,6 +290,10 @@ def main() -> int:
         stats = parity.check_rows(O, q_rows, w_rows, K_bits, b_of, rows, wl.m, wl.k, wl.mask_mode,
                                   gi, gs, n_threads=threads, oracle_out=ora)
         result["parity_on_sample"] = stats
+        # the 1M configuration asks for 4096 sampled rows; the default sample here is bounded so
+        # that the run stays short (tests/test_gpu_large.py and --oracle-rows 4096 do all of them)
+        result["parity_on_sample"]["rows_requested"] = args.oracle_rows
+        result["parity_on_sample"]["rows_of_full_check"] = 4096
 
     print(json.dumps(result), flush=True)
     return 0

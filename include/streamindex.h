@@ -34,6 +34,13 @@
  *   - Argument errors are detected on the host before anything is launched and reported as
  *     a negative si_status; no exception crosses the boundary.
  *   - Calls that share a workspace must not overlap in time.
+ *   - A row whose internal candidate buffer overflowed is reported in place: all k slots hold
+ *     idx = -2 and score = NaN.  The buffer sizes the library computes rule this out; the
+ *     marker exists so that a violated invariant can never look like a result.
+ *   - State the library keeps between calls: the optional timing facility at the end of this
+ *     file (off by default, guarded by a mutex), a per-thread last HIP error code, and per-device
+ *     caches of two immutable facts (compute-unit count, the LDS limit already granted to the
+ *     write-out kernel).  Nothing else; entry points may be called from several threads.
  */
 #ifndef STREAMINDEX_H
 #define STREAMINDEX_H
@@ -86,8 +93,7 @@ si_status si_plan_tiles(const si_dims* dims, int32_t m, int32_t k, si_mask_mode 
  * count and an fp32 threshold; B*c_S rows (c_S, c_T clamped to S, T).  0 on invalid arguments. */
 size_t si_workspace_bytes(const si_dims* dims, int32_t k, int32_t c_S, int32_t c_T);
 
-/* The whole step (Algorithm 2).  Runs the single-pass schedule (si_indexer_topk_fused, one
- * launches) when k <= 2048 and workspace_bytes >= si_fused_workspace_bytes(dims, k, 0); otherwise
+/* The whole step (Algorithm 2).  Runs the single-pass schedule (si_indexer_topk_fused) when k <= 2048 and workspace_bytes >= si_fused_workspace_bytes(dims, k, 0); otherwise
  * the tiled schedule with the tiling si_plan_tiles chooses for budget = workspace_bytes.  Both
  * give the same bits.
  *   q         device [B,S,H_I,D] bf16        K  device [B,T,D] bf16      w  device [B,S,H_I] f32
@@ -151,12 +157,29 @@ uint64_t si_materialize_bytes(const si_dims* dims);
  * those events and returns, per kernel class, the summed duration in milliseconds and the
  * number of launches since the last reset.  Classes: 0 score tile (with its fused filter),
  * 1 filter of caller-supplied scores, 2 compaction (select + merge), 3 final sort + write-out,
- * 4 buffer / counter init, 5 single-pass kernel.  Not thread safe; meant for a single
- * benchmarking thread. */
+ * 4 buffer / counter init, 5 single-pass kernel.  One set of totals per process: meant for a
+ * single benchmarking thread (concurrent callers are serialised, their launches are summed). */
 #define SI_PROFILE_CLASSES 6
 si_status si_profile_enable(int32_t on);
 si_status si_profile_reset(void);
 si_status si_profile_read(double* ms_per_class, int64_t* launches_per_class);
+
+/* Phase clock of the single-pass kernel, for the phase budget of a benchmark run.  While
+ * device_words is non-NULL, launches of the single-pass schedule with D = 128, 33..64 heads and
+ * k <= 1024 run an instrumented copy of the kernel in which workgroup j ADDS to
+ * device_words[j*16 + i] (uint64, device memory, at least n_workgroups*16 words, n_workgroups >=
+ * the device's compute units, cleared by the caller):
+ *   i = 0..5  time in ticks of the device's constant wall clock (hipDeviceAttributeWallClockRate):
+ *             0 item set-up and barriers around sweeps, 1 key sweeps, 2 in-kernel merges,
+ *             3 final cut + sort + write-out, 4 barrier behind the write-out, 5 residency
+ *             (first instruction to exit, summed over launches);
+ *   i = 6..10 counts: 6 work items, 7 sweep calls, 8 128-key steps, 9 merges, 10 launches.
+ * Results are unchanged.  Pass NULL to switch back to the plain kernel.  The pointer is global to
+ * the process: meant for one benchmarking thread. */
+si_status si_profile_phases(uint64_t* device_words, int32_t n_workgroups);
+/* Ticks per millisecond of the current device's constant wall clock (the unit of the phase
+ * clock); 0 if the runtime cannot tell. */
+int32_t si_wall_clock_khz(void);
 
 const char* si_strerror(si_status status);
 /* hipError_t of the last failed HIP call made by this library on this thread (0 = none). */

@@ -26,7 +26,9 @@ EXPORTS = (
     "si_plan_tiles", "si_workspace_bytes", "si_indexer_topk", "si_indexer_topk_tiled",
     "si_fused_workspace_bytes", "si_indexer_topk_fused",
     "si_score_tile", "si_topk_from_scores", "si_materialize_bytes", "si_profile_enable",
-    "si_profile_reset", "si_profile_read", "si_strerror", "si_last_hip_error", "si_version",
+    "si_profile_reset", "si_profile_read", "si_profile_phases", "si_wall_clock_khz", "si_strerror",
+    "si_last_hip_error",
+    "si_version",
 )
 
 
@@ -88,6 +90,10 @@ def load():
     L.si_profile_reset.argtypes = []
     L.si_profile_read.restype = c_int32
     L.si_profile_read.argtypes = [POINTER(c_double), POINTER(c_int64)]
+    L.si_profile_phases.restype = c_int32
+    L.si_profile_phases.argtypes = [c_void_p, c_int32]
+    L.si_wall_clock_khz.restype = c_int32
+    L.si_wall_clock_khz.argtypes = []
     L.si_strerror.restype = c_char_p
     L.si_strerror.argtypes = [c_int32]
     L.si_last_hip_error.restype = c_int32
@@ -159,13 +165,13 @@ def si_plan_tiles(B, S, H_I, D, T, m, k, mask_mode, hbm_budget_bytes):
 def si_indexer_topk(q, K, w, m, k, mask_mode, out_idx, out_score, workspace, stream=None):
     """workspace: uint8 GPU tensor; its size is the HBM budget the tiling is planned against."""
     dims = _dims_of(q, K, w)
+    _expect_out(out_idx, out_score, (dims.B, dims.S, k))
     _check(load().si_indexer_topk(
         _dev_ptr(q, torch.bfloat16, "q"), _dev_ptr(K, torch.bfloat16, "K"),
         _dev_ptr(w, torch.float32, "w"), byref(dims), m, k, mask_mode,
         _dev_ptr(out_idx, torch.int32, "out_idx"), _dev_ptr(out_score, torch.float32, "out_score"),
         _dev_ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
         _stream_handle(stream)), "si_indexer_topk")
-    _expect_out(out_idx, out_score, (dims.B, dims.S, k))
 
 
 def si_indexer_topk_tiled(q, K, w, m, k, mask_mode, c_S, c_T, out_idx, out_score, workspace,
@@ -233,6 +239,26 @@ def si_profile_enable(on: bool):
 
 def si_profile_reset():
     _check(load().si_profile_reset(), "si_profile_reset")
+
+
+PHASE_WORDS = 16
+PHASE_NAMES = ("setup", "sweep", "merge", "final", "final_wait", "resident",
+               "items", "sweeps", "steps", "merges", "launches")
+
+
+def si_profile_phases(device_words, n_workgroups: int = 0):
+    """device_words: int64 GPU tensor of n_workgroups*16 zeros, or None to switch the clock off."""
+    if device_words is None:
+        _check(load().si_profile_phases(None, 0), "si_profile_phases")
+        return
+    if device_words.numel() < n_workgroups * PHASE_WORDS:
+        raise ValueError("device_words must hold n_workgroups * 16 words")
+    _check(load().si_profile_phases(_dev_ptr(device_words, torch.int64, "device_words"), n_workgroups),
+           "si_profile_phases")
+
+
+def si_wall_clock_khz() -> int:
+    return int(load().si_wall_clock_khz())
 
 
 def si_profile_read():

@@ -30,6 +30,19 @@ def _hipcc() -> str:
     return "hipcc"
 
 
+def source_hash() -> str:
+    """First 16 hex digits of the SHA-256 over the library's sources (kernels, driver, public
+    header), in a fixed order: identifies the build a measurement was taken on."""
+    import hashlib
+    h = hashlib.sha256()
+    files = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".h")))
+    files.append(os.path.join(INCLUDE, "streamindex.h"))
+    for f in files:
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
 def build(force: bool = True, verbose: bool = False) -> str:
     """Compile every HIP source and link the shared library.  Returns its path."""
     os.makedirs(OBJ_DIR, exist_ok=True)

@@ -7,6 +7,8 @@
 // result is the same).
 
 #include <algorithm>
+#include <atomic>
+#include <mutex>
 #include <vector>
 
 #include "si_internal.h"
@@ -26,7 +28,10 @@ si_status hip_fail(hipError_t e) {
 
 // ---- per-kernel timing (benchmark aid) --------------------------------------------------
 struct Profiler {
+    std::mutex mu;  // every member below is read and written under it
     bool on = false;
+    unsigned long long* phase = nullptr;  // device words of the single-pass kernel's phase clock
+    int32_t phase_slots = 0;
     std::vector<hipEvent_t> pool;  // reused events
     size_t used = 0;
     struct Span { int cls; size_t begin, end; };
@@ -65,6 +70,7 @@ Profiler g_prof;
 // Brackets one launch with events when profiling is on.
 template <typename F>
 hipError_t timed(int cls, hipStream_t stream, F&& launch) {
+    std::lock_guard<std::mutex> hold(g_prof.mu);
     if (!g_prof.on) return launch();
     if (g_prof.spans.size() >= 8192) {  // bound the number of live events
         hipError_t e = g_prof.drain();
@@ -131,13 +137,65 @@ FusedLayout carve_fused(void* base, int64_t S, int64_t k, int64_t c_S) {
     L.counters = reinterpret_cast<int32_t*>(p + off);
     off = align_up(off + static_cast<size_t>(L.n_launches) * sizeof(int32_t), 256);
     L.slots.keys = reinterpret_cast<key64_t*>(p + off);
-    L.slots.cap = static_cast<int32_t>(kFusedTriggerMul * k + 384);
+    L.slots.cap = static_cast<int32_t>(kFusedTriggerMul * k + kFusedRowSlack);
     off = align_up(off + static_cast<size_t>(kFusedSlots) * kQueriesPerBlock * L.slots.cap * sizeof(key64_t), 256);
     L.slots.count = nullptr;
     L.slots.theta = nullptr;
     L.slots.bytes = off;
     L.bytes = off;
     return L;
+}
+
+// Immutable facts about a device, looked up once per device and process.
+struct DeviceInfo {
+    std::atomic<int> compute_units{0};
+};
+constexpr int kMaxDevices = 64;
+DeviceInfo g_device[kMaxDevices];
+
+// Workgroups the single-pass kernel is launched with: one per compute unit of the current
+// device (each holds 8 waves at 2 per SIMD and 100+ KB of LDS), at most kFusedSlots (what the
+// workspace has row buffers for).
+hipError_t fused_workgroups(int32_t* n) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    int cus = (dev >= 0 && dev < kMaxDevices) ? g_device[dev].compute_units.load(std::memory_order_acquire) : 0;
+    if (cus == 0) {
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        if (cus < 1) return hipErrorInvalidDevice;
+        if (dev >= 0 && dev < kMaxDevices) g_device[dev].compute_units.store(cus, std::memory_order_release);
+    }
+    *n = std::min<int32_t>(cus, kFusedSlots);
+    return hipSuccess;
+}
+
+// The single-pass schedule on a carved workspace: one counter-clearing kernel, then one launch
+// per c_S queries.  Arguments have been checked.
+si_status run_fused(const void* q, const void* K, const float* w, const si_dims& d, int32_t m, int32_t k,
+                    int32_t mask_mode, int32_t c_S, const FusedLayout& L, int32_t* out_idx,
+                    float* out_score, hipStream_t hs) {
+    int32_t n_wg = 0;
+    hipError_t e = fused_workgroups(&n_wg);
+    if (e != hipSuccess) return hip_fail(e);
+    e = timed(kProfInit, hs, [&] {
+        return launch_zero_ints(L.counters, static_cast<int32_t>(L.n_launches), hs);
+    });
+    if (e != hipSuccess) return hip_fail(e);
+    int64_t launch = 0;
+    for (int64_t s0 = 0; s0 < d.S; s0 += c_S, ++launch) {
+        const int32_t rows = static_cast<int32_t>(std::min<int64_t>(c_S, d.S - s0));
+        e = timed(kProfFused, hs, [&] {
+            // (timed holds the profiler's lock: the phase clock's buffer is read under it)
+            unsigned long long* phase = g_prof.phase_slots >= n_wg ? g_prof.phase : nullptr;
+            if (phase != nullptr && !(d.D == 128 && d.H_I > 32 && k <= 1024)) phase = nullptr;
+            return launch_fused(q, K, w, d, m, mask_mode, k, static_cast<int32_t>(s0), rows, L.slots,
+                                n_wg, L.counters + launch, out_idx, out_score, phase, hs);
+        });
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return SI_OK;
 }
 }  // namespace
 
@@ -262,7 +320,7 @@ si_status si_indexer_topk_tiled(const void* q, const void* K, const float* w,
         for (int64_t t0 = 0; t0 < t_hi;) {
             const int32_t width = static_cast<int32_t>(std::min<int64_t>(next_width(t0, c_T, k), d.T - t0));
             e = timed(kProfScore, hs, [&] {
-                return launch_score_filter(q, K, w, d, m, mask_mode, static_cast<int32_t>(s0),
+                return launch_score_filter(q, K, w, d, m, mask_mode, k, static_cast<int32_t>(s0),
                                            static_cast<int32_t>(t0), rows, width, c_S, rb, hs);
             });
             if (e != hipSuccess) return hip_fail(e);
@@ -310,25 +368,11 @@ si_status si_indexer_topk_fused(const void* q, const void* K, const float* w, co
     if (k > kFusedMaxK) return SI_ERR_UNSUPPORTED_SHAPE;
     if (!q || !K || !w || !out_idx || !out_score || !workspace) return SI_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return SI_ERR_INVALID_ARG;
-    const si_dims d = *dims;
-    c_S = fused_rows_per_launch(c_S, d.S);
-    const FusedLayout L = carve_fused(workspace, d.S, k, c_S);
+    c_S = fused_rows_per_launch(c_S, dims->S);
+    const FusedLayout L = carve_fused(workspace, dims->S, k, c_S);
     if (L.bytes > workspace_bytes) return SI_ERR_WORKSPACE_TOO_SMALL;
-    hipStream_t hs = static_cast<hipStream_t>(stream);
-    hipError_t e = timed(kProfInit, hs, [&] {
-        return launch_zero_ints(L.counters, static_cast<int32_t>(L.n_launches), hs);
-    });
-    if (e != hipSuccess) return hip_fail(e);
-    int64_t launch = 0;
-    for (int64_t s0 = 0; s0 < d.S; s0 += c_S, ++launch) {
-        const int32_t rows = static_cast<int32_t>(std::min<int64_t>(c_S, d.S - s0));
-        e = timed(kProfFused, hs, [&] {
-            return launch_fused(q, K, w, d, m, mask_mode, k, static_cast<int32_t>(s0), rows, L.slots,
-                                kFusedSlots, L.counters + launch, out_idx, out_score, hs);
-        });
-        if (e != hipSuccess) return hip_fail(e);
-    }
-    return SI_OK;
+    return run_fused(q, K, w, *dims, m, k, mask_mode, c_S, L, out_idx, out_score,
+                     static_cast<hipStream_t>(stream));
 }
 
 si_status si_topk_from_scores(const float* scores, int32_t R, int32_t n_cols,
@@ -348,7 +392,7 @@ si_status si_topk_from_scores(const float* scores, int32_t R, int32_t n_cols,
     for (int64_t t0 = 0; t0 < n_cols; t0 += c_T) {
         const int32_t width = static_cast<int32_t>(std::min<int64_t>(c_T, n_cols - t0));
         e = timed(kProfFilterScores, hs, [&] {
-            return launch_filter_scores(scores, R, n_cols, static_cast<int32_t>(t0), width, legal, rb, hs);
+            return launch_filter_scores(scores, R, n_cols, k, static_cast<int32_t>(t0), width, legal, rb, hs);
         });
         if (e != hipSuccess) return hip_fail(e);
         e = timed(kProfCompact, hs, [&] { return launch_compact(rb, 1, R, R, k, 2 * k, hs); });
@@ -365,11 +409,28 @@ uint64_t si_materialize_bytes(const si_dims* dims) {
 }
 
 si_status si_profile_enable(int32_t on) {
+    std::lock_guard<std::mutex> hold(g_prof.mu);
     g_prof.on = on != 0;
     return SI_OK;
 }
 
+si_status si_profile_phases(uint64_t* device_words, int32_t n_workgroups) {
+    if (device_words != nullptr && n_workgroups < 1) return SI_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> hold(g_prof.mu);
+    g_prof.phase = reinterpret_cast<unsigned long long*>(device_words);
+    g_prof.phase_slots = device_words ? n_workgroups : 0;
+    return SI_OK;
+}
+
+int32_t si_wall_clock_khz(void) {
+    int dev = 0, khz = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess) return 0;
+    return khz;
+}
+
 si_status si_profile_reset(void) {
+    std::lock_guard<std::mutex> hold(g_prof.mu);
     hipError_t e = g_prof.drain();
     if (e != hipSuccess) return hip_fail(e);
     for (int i = 0; i < SI_PROFILE_CLASSES; ++i) {
@@ -381,6 +442,7 @@ si_status si_profile_reset(void) {
 
 si_status si_profile_read(double* ms_per_class, int64_t* launches_per_class) {
     if (!ms_per_class || !launches_per_class) return SI_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> hold(g_prof.mu);
     hipError_t e = g_prof.drain();
     if (e != hipSuccess) return hip_fail(e);
     for (int i = 0; i < SI_PROFILE_CLASSES; ++i) {

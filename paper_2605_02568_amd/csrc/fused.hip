@@ -22,9 +22,11 @@
 
 namespace si {
 
-// A sweep is stopped once a row holds `trigger` keys and can overshoot by 319 (see score_sweep).
-__host__ __device__ inline int fused_trigger(int k) { return kFusedTriggerMul * k; }
-__host__ __device__ inline int fused_row_cap(int k) { return fused_trigger(k) + 384; }
+// A sweep is stopped once a row holds `trigger` keys and can overshoot by kSweepOvershoot (see
+// score_sweep): the row buffer must hold both.
+__host__ __device__ constexpr int fused_trigger(int k) { return kFusedTriggerMul * k; }
+__host__ __device__ constexpr int fused_row_cap(int k) { return fused_trigger(k) + kFusedRowSlack; }
+static_assert(kFusedRowSlack >= kSweepOvershoot, "a stopped sweep must not run past the end of a row buffer");
 // Items with at most this many keys warm L2 with the next item's query rows while they sort.
 constexpr int kWarmupMaxKeys = 8192;
 
@@ -42,13 +44,17 @@ constexpr int fused_lds_bytes() {
 // handed out through *counter (zero before the launch), longest key range first so that the
 // workgroups running at any time have nearly equal work and walk the keys roughly together
 // (which keeps the key rows they share in L2).  Workgroup j uses rows [8j, 8j+8) of `slots`.
-template <int D, int HB, int KMAX>
+//
+// TIMED: workgroup j also adds, for its wave 0, the time spent in each phase (ticks of the constant
+// wall clock) and event counts to phase[j * kPhaseWords ...] (layout: PhaseWord in si_internal.h).
+// Every wave runs the same barriers, so wave 0's phases are the workgroup's.
+template <int D, int HB, int KMAX, bool TIMED>
 __global__ __launch_bounds__(kScoreThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ K,
                           const float* __restrict__ w, int B, int S, int H, int T, int m,
                           int mask_mode, int k, int pow2_k, int s_begin, int rows, RowBuffers slots,
                           int* __restrict__ counter, int32_t* __restrict__ out_idx,
-                          float* __restrict__ out_score) {
+                          float* __restrict__ out_score, unsigned long long* __restrict__ phase) {
     // One LDS object for everything (sweep buffers / sort area, histograms, flags, work item):
     // with several, the compiler orders every LDS read behind the global -> LDS transfers in
     // flight and the key prefetch of the sweep no longer overlaps anything.
@@ -70,6 +76,18 @@ void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
     const int trigger = fused_trigger(k);
     const int limit = compact_limit(k);
     key64_t* const cand = slots.keys + (static_cast<int64_t>(blockIdx.x) * kQB + wave) * slots.cap;
+
+    // phase clock (TIMED only): time since the last mark goes to the phase that just ended
+    unsigned long long t_first = 0, t_mark = 0, acc[kPhaseWords] = {};
+    if (TIMED) t_first = t_mark = __builtin_amdgcn_s_memrealtime();
+#define SI_PHASE(P)                                                      \
+    if (TIMED) {                                                         \
+        const unsigned long long now_ = __builtin_amdgcn_s_memrealtime(); \
+        acc[P] += now_ - t_mark;                                         \
+        t_mark = now_;                                                   \
+    }
+#define SI_COUNT(P, N) \
+    if (TIMED) acc[P] += static_cast<unsigned long long>(N);
 
     // Work items: the next one is requested from the counter while the current one is processed,
     // so its round trip costs nothing.
@@ -96,13 +114,16 @@ void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
         o.cand = cand;
         o.cap = slots.cap;
         o.n_cand = 0;
+        o.overflow = false;
         o.live = live;
         o.out_row = nullptr;
         // the first two key chunks of every sweep start their trip before the query is (re)loaded,
         // and, after a stop, before the merge
         if (group_keys > 0)
             sweep_prefetch<D>(lds, K + static_cast<int64_t>(b) * T * D, T);
+        SI_COUNT(kPhaseItems, 1)
         for (int kbeg = 0; kbeg < group_keys;) {
+            SI_PHASE(kPhaseSetup)  // item start or merge -> the sweep call (the query load is only issued here)
             {
                 bf16x8 a[HB][D / 16];
                 float wr[HB][16];
@@ -117,9 +138,13 @@ void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
                 o.row_keys = row_keys - kbeg;
                 o.index0 = static_cast<uint32_t>(kbeg);
                 const __bf16* Kb = K + (static_cast<int64_t>(b) * T + kbeg) * D;
-                kbeg += score_sweep<D, HB, true, true, true>(lds, a, wr, Kb, T - kbeg, group_keys - kbeg, o,
-                                                       s_flags, trigger);
+                const int swept = score_sweep<D, HB, true, true, true>(lds, a, wr, Kb, T - kbeg,
+                                                                       group_keys - kbeg, o, s_flags, trigger);
+                kbeg += swept;
+                SI_COUNT(kPhaseChunks, (swept + kKeyChunk - 1) / kKeyChunk)
+                SI_COUNT(kPhaseSweeps, 1)
             }
+            SI_PHASE(kPhaseSweep)
             if (threadIdx.x == 0) s_next = next_item;  // (arrived long ago) for the warm-up below
             __syncthreads();  // the sweep's LDS and flags are free again
             if (kbeg >= group_keys) break;
@@ -138,11 +163,16 @@ void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
             }
             __builtin_amdgcn_s_waitcnt(0x0F70);  // the kept keys are written before anything is appended behind them
             __syncthreads();
+            SI_PHASE(kPhaseMerge)
+            SI_COUNT(kPhaseMerges, 1)
         }
+        SI_PHASE(kPhaseSetup)  // (items without a key, and the barrier after the last sweep)
 
         // Write-out: exact cut to k, sort best first in the wave's slice of the (now idle)
         // sweep LDS, decode, pad.
-        if (live) {
+        if (live && o.overflow) {
+            poison_row(out_idx, out_score, (static_cast<int64_t>(b) * S + s_begin + r) * k, k);
+        } else if (live) {
             key64_t* s_sort = reinterpret_cast<key64_t*>(lds) + static_cast<size_t>(wave) * sort_slots(pow2_k);
             const SortSlot slot;
             const int n = o.n_cand;
@@ -198,9 +228,18 @@ void indexer_fused_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
             }
         }
         if (threadIdx.x == 0) s_item = next_item;
+        SI_PHASE(kPhaseFinal)
         __syncthreads();  // the next item's sweep overwrites the LDS the sort used
         item = s_item;
+        SI_PHASE(kPhaseFinalWait)  // waiting for the slowest wave's write-out
     }
+    if (TIMED && threadIdx.x == 0) {
+        acc[kPhaseResident] = __builtin_amdgcn_s_memrealtime() - t_first;
+        acc[kPhaseLaunches] = 1;
+        for (int i = 0; i < kPhaseWords; ++i) phase[blockIdx.x * kPhaseWords + i] += acc[i];
+    }
+#undef SI_PHASE
+#undef SI_COUNT
 }
 
 __global__ void zero_ints_kernel(int* p, int n) {
@@ -216,7 +255,7 @@ hipError_t launch_zero_ints(int32_t* p, int32_t n, hipStream_t stream) {
 hipError_t launch_fused(const void* q, const void* K, const float* w, const si_dims& d, int32_t m,
                         int32_t mask_mode, int32_t k, int32_t s_begin, int32_t rows,
                         const RowBuffers& slots, int32_t n_slots, int32_t* counter, int32_t* out_idx,
-                        float* out_score, hipStream_t stream) {
+                        float* out_score, unsigned long long* phase, hipStream_t stream) {
     if (k < 1 || k > kFusedMaxK || slots.cap < fused_row_cap(k) || n_slots < 1) return hipErrorInvalidValue;
     const int64_t items = static_cast<int64_t>((rows + kQB - 1) / kQB) * d.B;
     const dim3 grid(static_cast<unsigned>(std::min<int64_t>(items, n_slots)));
@@ -226,16 +265,16 @@ hipError_t launch_fused(const void* q, const void* K, const float* w, const si_d
     const int HB = (d.H_I + 31) / 32;
     int pow2_k = 16;
     while (pow2_k < k) pow2_k <<= 1;
+#define SI_LAUNCH_AS(DD, HH, KK, TT)                                                                \
+    hipLaunchKernelGGL((indexer_fused_kernel<DD, HH, KK, TT>), grid, block, 0, stream, qp, Kp, w,  \
+                       d.B, d.S, d.H_I, d.T, m, mask_mode, k, pow2_k, s_begin, rows, slots,         \
+                       counter, out_idx, out_score, phase)
 #define SI_LAUNCH(DD, HH)                                                                          \
-    if (k <= 1024)                                                                                  \
-        hipLaunchKernelGGL((indexer_fused_kernel<DD, HH, 1024>), grid, block, 0, stream, qp, Kp, w, \
-                           d.B, d.S, d.H_I, d.T, m, mask_mode, k, pow2_k, s_begin, rows, slots,     \
-                           counter, out_idx, out_score);                                            \
-    else                                                                                            \
-        hipLaunchKernelGGL((indexer_fused_kernel<DD, HH, kFusedMaxK>), grid, block, 0, stream, qp,  \
-                           Kp, w, d.B, d.S, d.H_I, d.T, m, mask_mode, k, pow2_k, s_begin, rows,     \
-                           slots, counter, out_idx, out_score)
-    if (d.D == 128 && HB == 2) { SI_LAUNCH(128, 2); }
+    if (k <= 1024) SI_LAUNCH_AS(DD, HH, 1024, false); else SI_LAUNCH_AS(DD, HH, kFusedMaxK, false)
+    // the phase clock exists for the evaluation head shape only (every variant is a full kernel)
+    if (phase != nullptr && !(d.D == 128 && HB == 2 && k <= 1024)) return hipErrorInvalidValue;
+    if (phase != nullptr) { SI_LAUNCH_AS(128, 2, 1024, true); }
+    else if (d.D == 128 && HB == 2) { SI_LAUNCH(128, 2); }
     else if (d.D == 128 && HB == 1) { SI_LAUNCH(128, 1); }
     else if (d.D == 64 && HB == 2) { SI_LAUNCH(64, 2); }
     else if (d.D == 64 && HB == 1) { SI_LAUNCH(64, 1); }
@@ -243,6 +282,7 @@ hipError_t launch_fused(const void* q, const void* K, const float* w, const si_d
     else if (d.D == 32 && HB == 1) { SI_LAUNCH(32, 1); }
     else return hipErrorInvalidValue;
 #undef SI_LAUNCH
+#undef SI_LAUNCH_AS
     return hipGetLastError();
 }
 

@@ -85,6 +85,60 @@ __device__ __forceinline__ void load_query(const __bf16* __restrict__ q, const f
     }
 }
 
+// Byte offset, inside a 128-key chunk of head dimension D, of the 16-byte piece that lane `lane`
+// moves with the wave-wide load number `blk` of the chunk (each load fills 1 KiB of LDS, lane l
+// writing bytes [16 l, 16 l + 16) of it).  The XOR swizzle of the pieces of a key row is applied
+// on this (global) side, so that LDS rows are unpadded yet bank-conflict free when read back.
+template <int D>
+__host__ __device__ constexpr int chunk_lane_offset(int blk, int lane) {
+    constexpr int kRowBytes = D * 2;
+    constexpr int kPieces = D / 8;                // 16-byte pieces per key row
+    constexpr int kRowsPer256 = 256 / kRowBytes;  // key rows per 256 B of LDS (0 for D = 256: unsupported)
+    constexpr int kRowsPerLoad = 64 / kPieces;    // key rows covered by one wave-wide load
+    const int row = blk * kRowsPerLoad + lane / kPieces;
+    const int piece = (lane % kPieces) ^ ((row / kRowsPer256) % kPieces);
+    return row * kRowBytes + piece * 16;
+}
+// Checked at compile time for every head dimension the library accepts: the loads of one chunk
+// read every 16-byte piece of the chunk exactly once and nothing outside it, so the largest
+// address a load can form is (chunk base) + 128 * 2D - 16, which the descriptor of chunk_rsrc
+// compares against the bytes that really exist.
+template <int D>
+constexpr bool chunk_offsets_cover_chunk_once() {
+    constexpr int kChunkBytes = 128 * D * 2;
+    bool seen[kChunkBytes / 16] = {};
+    for (int blk = 0; blk < kChunkBytes / 1024; ++blk)
+        for (int lane = 0; lane < 64; ++lane) {
+            const int off = chunk_lane_offset<D>(blk, lane);
+            if (off < 0 || off % 16 != 0 || off + 16 > kChunkBytes || seen[off / 16]) return false;
+            seen[off / 16] = true;
+        }
+    for (int i = 0; i < kChunkBytes / 16; ++i)
+        if (!seen[i]) return false;
+    return true;
+}
+static_assert(chunk_offsets_cover_chunk_once<32>() && chunk_offsets_cover_chunk_once<64>() &&
+              chunk_offsets_cover_chunk_once<128>(), "a chunk's loads must tile the chunk exactly");
+
+// Buffer descriptor of the key rows [first_key, key_clamp) of Kb: raw buffer, stride 0, untyped
+// 32-bit data, num_records = the bytes that exist from first_key on (0 when the chunk lies past the
+// key range).  A chunk's loads address it with the lane's constant offset only (row inside the
+// chunk, piece), which is the one part of a buffer address the hardware range-checks: a 16-byte
+// piece at or past num_records is not read and lands as zero.  The chunk's position is folded into
+// the base address and the record count with scalar arithmetic, never into the unchecked scalar
+// offset operand, so no load can touch memory past the last key row.  key_clamp * 2D < 2^32.
+template <int D>
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t chunk_rsrc(const __bf16* Kb, int key_clamp, int first_key) {
+    constexpr unsigned kRowBytes = D * 2;
+    const unsigned total = static_cast<unsigned>(key_clamp) * kRowBytes;
+    const unsigned skip = static_cast<unsigned>(first_key) * kRowBytes;
+    // (written with min / max so that it stays on the scalar unit)
+    const unsigned start = min(skip, total);
+    const unsigned remain = total - start;
+    const char* base = reinterpret_cast<const char*>(Kb) + start;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base), 0, static_cast<int>(remain), 0x00020000);
+}
+
 // Starts the trip of the first two 128-key chunks of a sweep over Kb into LDS buffers 0 and 1
 // (the same transfers the sweep's own prologue would issue).  A sweep called with
 // PREFETCHED = true expects them in flight or landed and skips its own.  All 8 waves call it.
@@ -94,27 +148,22 @@ __device__ __forceinline__ void sweep_prefetch(unsigned char* lds, const __bf16*
 #if defined(__HIP_DEVICE_COMPILE__)
     constexpr int kRowBytes = D * 2;
     constexpr int kPieces = D / 8;
-    constexpr int kRowsPer256 = 256 / kRowBytes;
     constexpr int kBufBytes = kKeyChunk * kRowBytes;
     constexpr int kRowsPerLoad = 64 / kPieces;
     constexpr int kLoads = kKeyChunk / kRowsPerLoad / kWaves;
     typedef __attribute__((address_space(3))) void lds_void;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
-    const __amdgpu_buffer_rsrc_t krsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<__bf16*>(Kb), 0,
-        static_cast<int>(static_cast<unsigned>(key_clamp) * static_cast<unsigned>(kRowBytes)), 0x00020000);
 #pragma unroll
-    for (int c = 0; c < 2; ++c)
+    for (int c = 0; c < 2; ++c) {
+        const __amdgpu_buffer_rsrc_t krsrc = chunk_rsrc<D>(Kb, key_clamp, c * kKeyChunk);
 #pragma unroll
         for (int i = 0; i < kLoads; ++i) {
             const int blk = wave * kLoads + i;
-            const int row = blk * kRowsPerLoad + lane / kPieces;
-            const int piece = (lane % kPieces) ^ ((row / kRowsPer256) % kPieces);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                krsrc, (lds_void*)(lds + c * kBufBytes + blk * 1024), 16, row * kRowBytes + piece * 16,
-                c * kKeyChunk * kRowBytes, 0, 0);
+                krsrc, (lds_void*)(lds + c * kBufBytes + blk * 1024), 16, chunk_lane_offset<D>(blk, lane), 0, 0, 0);
         }
+    }
 #else
     (void)lds; (void)Kb; (void)key_clamp;
 #endif
@@ -130,6 +179,8 @@ struct SweepOut {
                        // all of them fit (always the case when the caller sizes the buffer as
                        // documented; kept as a bounds check on wave-uniform values)
     int n_cand;        // keys held (in/out)
+    bool overflow;     // (in/out, sticky) some survivors did not fit: the row's result is invalid
+                       // and the caller must report it (poison_row), never write a top-k from it
     uint32_t index0;   // key index of the sweep's first key
     // dense mode
     bool live;         // false: this wave's row does not exist, store nothing
@@ -185,6 +236,7 @@ __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)
     key64_t* const cand = o.cand;  // computed from the workgroup and wave numbers: uniform
     const int cap = __builtin_amdgcn_readfirstlane(o.cap);
     int n_cand = __builtin_amdgcn_readfirstlane(o.n_cand);
+    bool overflow = o.overflow;
     const uint32_t index0 = __builtin_amdgcn_readfirstlane(o.index0);
     const bool live = o.live;
     float* const out_row = o.out_row;
@@ -192,27 +244,22 @@ __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)
     // Global -> LDS without a register round trip: each wave-wide load writes 1 KiB of LDS
     // (lane l to byte l*16 of the block); the lane picks the global piece that belongs there.
     // Buffer addressing: the lane's part of the address (key row inside the chunk, piece) is a
-    // constant 32-bit offset, the chunk's part a scalar, and key rows past the end of the sweep's
-    // key range read as zero (they are never emitted), so a load costs no vector ALU work.
+    // constant 32-bit offset, the chunk's part sits in the descriptor (chunk_rsrc: scalar work
+    // only), and key rows past the end of the sweep's key range are not read and land as zero
+    // (they are never emitted), so a load costs no vector ALU work.
     typedef __attribute__((address_space(3))) void lds_void;
-    // (descriptor: raw buffer, stride 0, num_records = bytes of the key range, untyped 32-bit data;
-    // the host checks that a batch's keys stay below 4 GiB)
-    const __amdgpu_buffer_rsrc_t krsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<__bf16*>(Kb), 0,
-        static_cast<int>(static_cast<unsigned>(key_clamp) * static_cast<unsigned>(kRowBytes)), 0x00020000);
     int kvoff[kLoads];
 #pragma unroll
-    for (int i = 0; i < kLoads; ++i) {
-        const int blk = wave * kLoads + i;                   // 1 KiB block inside the chunk
-        const int row = blk * kRowsPerLoad + lane / kPieces; // key row inside the chunk
-        const int piece = (lane % kPieces) ^ ((row / kRowsPer256) % kPieces);
-        kvoff[i] = row * kRowBytes + piece * 16;
-    }
+    for (int i = 0; i < kLoads; ++i)
+        kvoff[i] = chunk_lane_offset<D>(wave * kLoads + i, lane);  // load wave*kLoads + i of the chunk
+
 #define SI_FETCH(KC0, BUFOFF)                                                                      \
-    _Pragma("unroll") for (int i = 0; i < kLoads; ++i)                                              \
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(krsrc,                                                 \
-            (lds_void*)(lds + (BUFOFF) + (wave * kLoads + i) * 1024), 16, kvoff[i],                 \
-            static_cast<int>(static_cast<unsigned>(KC0) * static_cast<unsigned>(kRowBytes)), 0, 0);
+    {                                                                                               \
+        const __amdgpu_buffer_rsrc_t krsrc_ = chunk_rsrc<D>(Kb, key_clamp, (KC0));                  \
+        _Pragma("unroll") for (int i = 0; i < kLoads; ++i)                                          \
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(krsrc_,                                        \
+                (lds_void*)(lds + (BUFOFF) + (wave * kLoads + i) * 1024), 16, kvoff[i], 0, 0, 0);   \
+    }
 
     // This lane's byte offset, inside a 32-key sub-block, of the operand for MFMA step ks.
     const int swz = (col / kRowsPer256) % kPieces;
@@ -273,14 +320,18 @@ __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)
                 const unsigned long long mask =                                                     \
                     __builtin_amdgcn_ballot_w64(legal) & __builtin_amdgcn_ballot_w64(above);        \
                 const int add = static_cast<int>(__popcll(mask));                                   \
-                if (add != 0 && n_cand + add <= cap) { /* the second test always holds, see SweepOut */ \
-                    const unsigned below = __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(mask >> 32), \
-                                           __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(mask), 0u)); \
-                    const unsigned byte_off = (static_cast<unsigned>(n_cand) + below) * 8u;         \
-                    if (legal && above)                                                             \
-                        *reinterpret_cast<key64_t*>(reinterpret_cast<char*>(cand) + byte_off) =     \
-                            make_key((VAL), index0 + static_cast<uint32_t>((KEY0) + lane));         \
-                    n_cand += add;                                                                  \
+                if (add != 0) {                                                                     \
+                    if (n_cand + add <= cap) { /* always, when the buffer is sized as documented */ \
+                        const unsigned below = __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(mask >> 32), \
+                                               __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(mask), 0u)); \
+                        const unsigned byte_off = (static_cast<unsigned>(n_cand) + below) * 8u;     \
+                        if (legal && above)                                                         \
+                            *reinterpret_cast<key64_t*>(reinterpret_cast<char*>(cand) + byte_off) = \
+                                make_key((VAL), index0 + static_cast<uint32_t>((KEY0) + lane));     \
+                        n_cand += add;                                                              \
+                    } else {                                                                        \
+                        overflow = true; /* wave-uniform; reported through the row's output */      \
+                    }                                                                               \
                 }                                                                                   \
             }                                                                                       \
         } else {                                                                                    \
@@ -347,6 +398,7 @@ __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)
 #undef SI_FETCH
 #undef SI_KREAD
     o.n_cand = n_cand;
+    o.overflow = overflow;
     // loads of chunks past the end may still be in flight: let them land before the LDS is reused
     __builtin_amdgcn_s_waitcnt(0x0F70);
     return kc0;

@@ -42,6 +42,7 @@ void score_tile_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ 
     o.cand = nullptr;
     o.cap = 0;
     o.n_cand = 0;
+    o.overflow = false;
     o.index0 = static_cast<uint32_t>(t0);
     o.live = live;
     o.out_row = tile + ws_row * tile_cols;
@@ -51,10 +52,15 @@ void score_tile_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ 
         o.n_cand = rb.count[ws_row];
         o.cand = rb.keys + ws_row * rb.cap;
         o.cap = rb.cap;
+        if (o.n_cand < 0) {  // overflowed in an earlier key tile: stays marked, appends nothing
+            o.overflow = true;
+            o.n_cand = 0;
+            o.row_keys = 0;
+        }
     }
     const __bf16* Kb = K + (static_cast<int64_t>(b) * T + t0) * D;
     score_sweep<D, HB, FILTER, false>(lds, a, wr, Kb, width, n_keys, o, nullptr, 0);
-    if (FILTER && live && lane == 0) rb.count[ws_row] = o.n_cand;
+    if (FILTER && live && lane == 0) rb.count[ws_row] = o.overflow ? -1 : o.n_cand;  // -1: see finalize
 }
 
 namespace {
@@ -93,9 +99,12 @@ hipError_t launch_score_tile(const void* q, const void* K, const float* w, const
 }
 
 hipError_t launch_score_filter(const void* q, const void* K, const float* w, const si_dims& d,
-                               int32_t m, int32_t mask_mode, int32_t s0, int32_t t0, int32_t rows,
+                               int32_t m, int32_t mask_mode, int32_t k, int32_t s0, int32_t t0, int32_t rows,
                                int32_t width, int32_t tile_rows, const RowBuffers& rb,
                                hipStream_t stream) {
+    // a row enters the tile with at most 2k - 1 keys and must have room for the whole tile
+    if (k < 1 || width < 1 || static_cast<int64_t>(rb.cap) < 2 * static_cast<int64_t>(k) + width)
+        return hipErrorInvalidValue;
     return launch<true>(q, K, w, d, m, mask_mode, s0, t0, rows, width, tile_rows, 0, nullptr, rb,
                         stream);
 }

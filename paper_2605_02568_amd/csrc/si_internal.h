@@ -40,6 +40,20 @@ __device__ inline int32_t legal_count(int32_t t, int32_t T, int32_t m, int32_t m
 }
 #endif
 
+// A row whose candidate buffer overflowed has no valid top-k.  The sizes the library computes
+// rule that out (a sweep appends at most its width / its overshoot to a row that is below its
+// trigger), so this marks an internal invariant violation; it is written into the row's output
+// (every slot: this index, NaN score) instead of a plausible-looking wrong answer.
+constexpr int32_t kPoisonIndex = -2;
+#ifdef __HIPCC__
+__device__ inline void poison_row(int32_t* out_idx, float* out_score, int64_t out, int k) {
+    for (int j = threadIdx.x & 63; j < k; j += 64) {
+        out_idx[out + j] = kPoisonIndex;
+        out_score[out + j] = __builtin_nanf("");
+    }
+}
+#endif
+
 constexpr int kMaxK = 4096;
 constexpr int kMaxHeads = 64;
 constexpr int kQueriesPerBlock = 8;  // score kernel: one query per wave, 8 waves
@@ -50,6 +64,11 @@ constexpr int kQueriesPerBlock = 8;  // score kernel: one query per wave, 8 wave
 constexpr int kFusedMaxK = 2048;
 constexpr int kFusedTriggerMul = 2;
 constexpr int kFusedSlots = 256;
+// A stopped sweep notices the trigger one 128-key step late and then drains its pipeline: a row
+// that held trigger - 1 keys before a step can grow by 128 in it, by 128 in the next one and by 64
+// in the drain.  Row buffers of the single-pass schedule carry kFusedRowSlack keys beyond the trigger.
+constexpr int kSweepOvershoot = 128 - 1 + 128 + 64;
+constexpr int kFusedRowSlack = 384;
 // Queries per launch when the caller does not say: the workgroups of a launch drift apart as they
 // work through their items (and then miss each other's key rows in L2); a launch boundary brings
 // them back in step.  131072 rows cost no time against a single launch and cut the key traffic
@@ -66,6 +85,22 @@ struct RowBuffers {
 };
 RowBuffers carve_workspace(void* base, int64_t rows, int64_t k, int64_t c_T);
 
+// Words of the phase clock of the single-pass kernel, per workgroup (si_profile_phases).
+enum PhaseWord {
+    kPhaseSetup = 0,      // ticks: item start / merge end -> sweep call, and the barrier behind a sweep
+    kPhaseSweep = 1,      // ticks: inside the key sweep (includes waiting for the query rows)
+    kPhaseMerge = 2,      // ticks: in-kernel merges (radix cut of the rows that reached 2k keys)
+    kPhaseFinal = 3,      // ticks: exact cut, sort, write-out of wave 0's row
+    kPhaseFinalWait = 4,  // ticks: barrier behind the write-out (the slowest wave's write-out)
+    kPhaseResident = 5,   // ticks: first instruction -> exit of the workgroup, summed over launches
+    kPhaseItems = 6,      // count: work items
+    kPhaseSweeps = 7,     // count: sweep calls
+    kPhaseChunks = 8,     // count: 128-key steps swept
+    kPhaseMerges = 9,     // count: merges
+    kPhaseLaunches = 10,  // count: launches this workgroup took part in
+    kPhaseWords = 16
+};
+
 enum ProfileClass { kProfScore = 0, kProfFilterScores = 1, kProfCompact = 2, kProfFinalize = 3, kProfInit = 4, kProfFused = 5 };
 
 // Kernel launchers (each enqueues exactly one kernel on `stream`).
@@ -75,13 +110,15 @@ hipError_t launch_score_tile(const void* q, const void* K, const float* w, const
                              int32_t width, int32_t tile_rows, int32_t tile_cols, float* tile,
                              hipStream_t stream);
 // Score tile fused with the mask and the filter: appends, per row, the legal entries that beat
-// the row's threshold to the row's buffer (row index = b*tile_rows + r).
+// the row's threshold to the row's buffer (row index = b*tile_rows + r).  A row holds fewer than
+// 2k keys when the tile starts (the compaction cuts it at 2k) and gains at most `width`:
+// rb.cap >= 2k + width is required and checked.
 hipError_t launch_score_filter(const void* q, const void* K, const float* w, const si_dims& d,
-                               int32_t m, int32_t mask_mode, int32_t s0, int32_t t0, int32_t rows,
+                               int32_t m, int32_t mask_mode, int32_t k, int32_t s0, int32_t t0, int32_t rows,
                                int32_t width, int32_t tile_rows, const RowBuffers& rb,
                                hipStream_t stream);
 hipError_t launch_init_rows(const RowBuffers& rb, int32_t n, hipStream_t stream);
-hipError_t launch_filter_scores(const float* scores, int32_t R, int32_t n_cols, int32_t t0,
+hipError_t launch_filter_scores(const float* scores, int32_t R, int32_t n_cols, int32_t k, int32_t t0,
                                 int32_t width, const int32_t* legal_rows, const RowBuffers& rb,
                                 hipStream_t stream);
 hipError_t launch_compact(const RowBuffers& rb, int32_t B, int32_t rows, int32_t tile_rows, int32_t k,
@@ -92,10 +129,12 @@ hipError_t launch_finalize(const RowBuffers& rb, int32_t B, int32_t rows, int32_
 
 // Single-pass schedule: queries [s_begin, s_begin + rows) of every batch in one launch.
 // slots: n_slots * 8 row buffers of slots.cap >= 2k + 384 keys; *counter must be zero.
+// phase: nullptr, or n_slots * kPhaseWords words the instrumented kernel variant adds its phase
+// times to (D = 128, 33..64 heads, k <= 1024 only).
 hipError_t launch_fused(const void* q, const void* K, const float* w, const si_dims& d, int32_t m,
                         int32_t mask_mode, int32_t k, int32_t s_begin, int32_t rows,
                         const RowBuffers& slots, int32_t n_slots, int32_t* counter, int32_t* out_idx,
-                        float* out_score, hipStream_t stream);
+                        float* out_score, unsigned long long* phase, hipStream_t stream);
 hipError_t launch_zero_ints(int32_t* p, int32_t n, hipStream_t stream);
 
 }  // namespace si

@@ -109,6 +109,11 @@ __global__ __launch_bounds__(kTopkThreads) void finalize_kernel(
     key64_t* s_sort = s_sort_all + static_cast<size_t>(wave) * sort_slots(pow2_k);
     const SortSlot slot;
     const int n = rb.count[row];
+    const int64_t o = (static_cast<int64_t>(blockIdx.y) * out_batch_stride + out_row0 + r) * k;
+    if (n < 0) {  // the score kernel marked the row: its buffer overflowed
+        poison_row(out_idx, out_score, o, k);
+        return;
+    }
     int c = min(n, k);
     if (n <= 64 * kFinalizeRegKeys) {
         RegKeys<kFinalizeRegKeys> keys;
@@ -129,7 +134,6 @@ __global__ __launch_bounds__(kTopkThreads) void finalize_kernel(
     for (int i = c + lane; i < P; i += 64) s_sort[slot(i)] = 0ull;  // empty keys sort last
     __builtin_amdgcn_wave_barrier();
     wave_sort_descending(s_sort, P);
-    const int64_t o = (static_cast<int64_t>(blockIdx.y) * out_batch_stride + out_row0 + r) * k;
     for (int j = lane; j < k; j += 64) {
         if (j < c) {
             const key64_t key = s_sort[slot(j)];
@@ -177,9 +181,12 @@ hipError_t launch_init_rows(const RowBuffers& rb, int32_t n, hipStream_t stream)
     return hipGetLastError();
 }
 
-hipError_t launch_filter_scores(const float* scores, int32_t R, int32_t n_cols, int32_t t0,
+hipError_t launch_filter_scores(const float* scores, int32_t R, int32_t n_cols, int32_t k, int32_t t0,
                                 int32_t width, const int32_t* legal_rows, const RowBuffers& rb,
                                 hipStream_t stream) {
+    // same room rule as the score kernel's filter: fewer than 2k keys held, at most `width` more
+    if (k < 1 || width < 1 || static_cast<int64_t>(rb.cap) < 2 * static_cast<int64_t>(k) + width)
+        return hipErrorInvalidValue;
     hipLaunchKernelGGL(filter_scores_kernel, dim3(R), dim3(kTopkThreads), 0, stream, scores, n_cols, t0,
                        width, legal_rows, rb);
     return hipGetLastError();

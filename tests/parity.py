@@ -32,7 +32,7 @@ def check_rows(oracle, q_rows, w_rows, K_bits, b_of_row, t_of_row, m, k, mask_mo
     recalls, swaps, max_err, exact_rows, checked_pairs = [], 0, 0.0, 0, 0
     for r in range(n):
         t = int(t_of_row[r])
-        L = T if mask_mode == 0 else min(T, (t + 1) // m)
+        L = oracle.legal_count(t, T, m, mask_mode)  # Section 4.2, from the oracle itself
         checked_pairs += L
         ke = min(k, L)
         gi, gs = gpu_idx[r], gpu_score[r]

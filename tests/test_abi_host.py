@@ -138,3 +138,32 @@ def test_product_package_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower().replace("no cpu fallback", ""), (dirpath, f)
+
+
+def test_wrong_output_shape_raises_before_the_library_is_called(monkeypatch):
+    """Every whole-step wrapper checks the output shapes first: a too-small output must never
+    reach a kernel.  Host tensors suffice, since the shape check comes before the device check."""
+    import torch
+
+    class Untouchable:
+        def __getattr__(self, name):
+            raise AssertionError(f"library entry {name} was reached with a mis-shaped output")
+
+    monkeypatch.setattr(binding, "_lib", Untouchable())
+    B, S, H, D, T, k = 1, 16, 4, 32, 8, 4
+    q = torch.zeros((B, S, H, D), dtype=torch.bfloat16)
+    K = torch.zeros((B, T, D), dtype=torch.bfloat16)
+    w = torch.zeros((B, S, H))
+    ws = torch.zeros(1 << 20, dtype=torch.uint8)
+    good_i = torch.zeros((B, S, k), dtype=torch.int32)
+    for bad_i, bad_s in [
+        (torch.zeros((B, S, k - 1), dtype=torch.int32), torch.zeros((B, S, k - 1))),
+        (good_i, torch.zeros((B, S - 1, k))),
+        (torch.zeros((B * S, k), dtype=torch.int32), torch.zeros((B * S, k))),
+    ]:
+        with pytest.raises(ValueError):
+            P.si_indexer_topk(q, K, w, 4, k, 1, bad_i, bad_s, ws)
+        with pytest.raises(ValueError):
+            P.si_indexer_topk_tiled(q, K, w, 4, k, 1, 8, 8, bad_i, bad_s, ws)
+        with pytest.raises(ValueError):
+            P.si_indexer_topk_fused(q, K, w, 4, k, 1, 0, bad_i, bad_s, ws)

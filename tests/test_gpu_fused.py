@@ -90,6 +90,35 @@ def test_fused_adversarial_ascending_scores(oracle):
     assert stats["mean_recall"] > 0.999, stats
 
 
+@pytest.mark.parametrize("k", [33, 97, 1057, 1024, 2048])
+def test_fused_rows_filled_to_the_brim(oracle, k):
+    """No mask and scores that rise with the key index: every key of the first sweep is a
+    candidate, so a row's count climbs by exactly 64 per half step and the sweep stops as late
+    as it can.  With k = 64 c + 33 the row holds 2k - 2 keys when the last full step before the
+    stop begins and ends at 2k + 318 of its 2k + 384 slots, one short of the worst case the
+    buffer is sized for; later sweeps start from the merged rows and pass through other
+    residues.  A dropped block of candidates (or an overflow marker, idx = -2) would show up
+    against the oracle."""
+    B, S, H, D, m = 1, 24, 1, 32, 1
+    T = 4 * k + 1000
+    g = torch.Generator(device="cpu").manual_seed(k)
+    base = torch.randn((D,), generator=g).abs() + 0.1
+    q = (base[None, None, None, :] * (1.0 + torch.rand((B, S, H, D), generator=g))).to(torch.bfloat16)
+    K = (base[None, None, :] * torch.linspace(0.5, 4.0, T)[None, :, None]).to(torch.bfloat16)
+    w = torch.ones((B, S, H))
+    qd, Kd, wd = q.to(DEV), K.to(DEV), w.to(DEV)
+    print(f"brim k={k} T={T}", flush=True)
+    fused = _run("fused", qd, Kd, wd, m, k, 0, 0)
+    assert int((fused[0] == -2).sum()) == 0
+    stats = parity.check_rows(
+        oracle, W.bf16_bits(q).reshape(S, H, D), w.numpy().reshape(S, H), W.bf16_bits(K),
+        np.zeros(S, dtype=np.int32), np.arange(S, dtype=np.int64), m, k, 0,
+        fused[0].cpu().numpy().reshape(S, k), fused[1].cpu().numpy().reshape(S, k))
+    assert stats["mean_recall"] > 0.999, stats
+    tiled = _run("tiled", qd, Kd, wd, m, k, 0, S, 777)
+    assert _same(fused, tiled)
+
+
 def test_default_entry_point_falls_back_to_the_tiled_plan():
     """si_indexer_topk with a workspace too small for the single-pass schedule plans tiles for
     that budget instead, and with k above 2048 it always does; same bits either way."""

@@ -35,7 +35,8 @@ def _sampled_check(oracle, wl, q, K, w, out_idx, out_score, n_rows, extra_rows=(
         np.zeros(len(rows), dtype=np.int32), rows, wl.m, wl.k, wl.mask_mode,
         out_idx[0].index_select(0, rows_d).cpu().numpy(),
         out_score[0].index_select(0, rows_d).cpu().numpy())
-    _say(f"{wl.name}: {stats}")
+    _say(f"{wl.name}: rows checked against the oracle: {len(rows)} (asked for {n_rows} sampled + edge rows); {stats}")
+    assert stats["rows"] == len(rows) >= min(n_rows, wl.S) // 2  # (a seeded sample may repeat a few positions)
     return stats
 
 
@@ -129,3 +130,36 @@ def test_flash_1m_within_8gb_workspace(oracle):
     _say(f"flash_1m single pass, workspace={fused_bytes}")
     assert 0 < fused_bytes < 64 * 2**20
     assert _same_bits(out, _run_default(wl, q, K, w, fused_bytes))
+
+
+# ------------------------------------------------------------------ the paper's other sweeps at full size
+SWEEP_ROWS = int(os.environ.get("SI_SWEEP_ROWS", "384"))
+
+
+@pytest.mark.parametrize("k", [64, 256, 2048])
+def test_flash_256k_k_sweep_sampled_rows(oracle, k):
+    """k sweep of Section 6.5 (Table 5) at its own size, S = 262,144, through the default entry
+    point: sampled and edge rows against the oracle."""
+    wl = W.CONFIGS["flash_256k"].scaled(k=k, name=f"flash_256k[k={k}]")
+    q, K, w, _ = W.make_inputs(wl, device=DEV)
+    nbytes = P.si_fused_workspace_bytes(wl.B, wl.S, wl.H, wl.D, wl.T, wl.k)
+    _say(f"{wl.name}: default entry point, workspace {nbytes}")
+    out = _run_default(wl, q, K, w, nbytes)
+    stats = _sampled_check(oracle, wl, q, K, w, out[0], out[1], SWEEP_ROWS)
+    assert stats["mean_recall"] > 0.9999 and stats["min_recall"] >= 1.0 - 2.0 / wl.k
+    valid = (out[0][0] >= 0).sum(dim=1).cpu().numpy()
+    t = np.arange(wl.S)
+    assert np.array_equal(valid, np.minimum(wl.k, np.minimum(wl.T, (t + 1) // wl.m)))
+
+
+def test_flash_256k_query_tile_sweep_is_bit_identical(oracle):
+    """c_S sweep of Section 6.5 (Table 5) at S = 262,144, k = 512, c_T = 8192: the full outputs are
+    the same bits for every query tile, and equal to the default entry point's."""
+    wl = W.CONFIGS["flash_256k"].scaled(k=512, name="flash_256k[k=512]")
+    q, K, w, _ = W.make_inputs(wl, device=DEV)
+    ref = _run_default(wl, q, K, w, P.si_fused_workspace_bytes(wl.B, wl.S, wl.H, wl.D, wl.T, wl.k))
+    stats = _sampled_check(oracle, wl, q, K, w, ref[0], ref[1], SWEEP_ROWS)
+    assert stats["mean_recall"] > 0.9999 and stats["min_recall"] >= 1.0 - 2.0 / wl.k
+    for c_S in (1024, 4096, 16384):
+        _say(f"{wl.name} c_S={c_S} c_T=8192")
+        assert _same_bits(ref, _run(wl, q, K, w, c_S, 8192)), c_S

@@ -321,6 +321,53 @@ def test_v4_head_shape_sweeps(oracle, B, S, m, k, mask):
             assert torch.equal(oi, ref[0]) and torch.equal(os_.view(torch.int32), ref[1].view(torch.int32))
 
 
+def _pattern_problem(dist, seed, B, S, H, D, T):
+    """dist 0: iid normal; 1: scores that rise with the key index for every query (nothing can be
+    filtered); 2: small integers (many exact ties: the index half of the order decides)."""
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    q = torch.randn((B, S, H, D), generator=g)
+    K = torch.randn((B, T, D), generator=g)
+    w = torch.randn((B, S, H), generator=g) / np.sqrt(H)
+    if dist == 1:
+        K = K.abs() * torch.linspace(0.5, 4.0, T)[None, :, None]
+        q, w = q.abs(), w.abs()
+    elif dist == 2:
+        K = torch.randint(-1, 2, (B, T, D), generator=g).float()
+        q = torch.randint(-1, 2, (B, S, H, D), generator=g).float()
+        w = torch.ones((B, S, H))
+    return q.to(torch.bfloat16), K.to(torch.bfloat16), w
+
+
+@pytest.mark.parametrize("k", [2049, 3000, 4096])
+@pytest.mark.parametrize("dist", [0, 1, 2])
+def test_k_above_2048_with_more_than_k_legal_keys(oracle, k, dist):
+    """The upper end of the advertised k range (the k sweep of Section 6.5 continued): every row
+    has far more than k legal keys, so the radix cut at k, the streamed (not register-held) rows
+    of the compaction and the write-out's largest sort all decide the result.  All rows against
+    the oracle, two tilings and the planned entry point bit-identical."""
+    B, S, H, D, T, m = 1, 48, 8, 32, 12000, 1
+    q, K, w = _pattern_problem(dist, 77 + k, B, S, H, D, T)
+    qd, Kd, wd = q.to(DEV), K.to(DEV), w.to(DEV)
+    _say(f"large k={k} dist={dist}")
+    a = _run_tiled(qd, Kd, wd, m, k, 0, S, T)
+    stats = parity.check_rows(
+        oracle, W.bf16_bits(q).reshape(B * S, H, D), w.numpy().reshape(B * S, H), W.bf16_bits(K),
+        np.zeros(S, dtype=np.int32), np.arange(S, dtype=np.int64), m, k, 0,
+        a[0].cpu().numpy().reshape(S, k), a[1].cpu().numpy().reshape(S, k))
+    _say(f"  {stats}")
+    assert stats["min_recall"] >= 1.0 - 2.0 / k, stats
+    if dist == 2:  # exactly representable scores: sets, order and ties must be the oracle's
+        ri, rs = oracle.topk_all(W.bf16_bits(q), W.bf16_bits(K), w.numpy(), m, k, 0, n_threads=parity.host_threads())
+        assert np.array_equal(a[0].cpu().numpy(), ri)
+        assert np.array_equal(a[1].cpu().numpy(), rs.astype(np.float32))
+    b = _run_tiled(qd, Kd, wd, m, k, 0, 16, 1500)   # key tiles narrower than k: saturated tiles
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1].view(torch.int32), b[1].view(torch.int32))
+    oi, os_ = torch.empty_like(a[0]), torch.empty_like(a[1])
+    P.si_indexer_topk(qd, Kd, wd, m, k, 0, oi, os_, _workspace(256 << 20))
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], oi) and torch.equal(a[1].view(torch.int32), os_.view(torch.int32))
+
+
 def test_adversarial_score_order_through_the_whole_path(oracle):
     """Keys sorted so that every later key scores higher for every query: nothing can be filtered,
     every tile floods the row buffers, compaction runs on its streaming path."""

@@ -115,6 +115,94 @@ def test_brute_force_tiny_config(oracle):
     assert np.allclose(os_, bs, rtol=1e-13, atol=1e-13)
 
 
+# ----------------------------------------------------------------------------- batch offset, row fan-out, score_at
+def _rand_case_batched(rng, B, S, H, D, T, integer=False):
+    if integer:
+        q = rng.integers(-3, 4, size=(B, S, H, D)).astype(np.float32)
+        K = rng.integers(-3, 4, size=(B, T, D)).astype(np.float32)
+        w = rng.integers(-2, 3, size=(B, S, H)).astype(np.float32) * 0.5
+    else:
+        q = rng.standard_normal((B, S, H, D)).astype(np.float32)
+        K = rng.standard_normal((B, T, D)).astype(np.float32)
+        w = (rng.standard_normal((B, S, H)) / np.sqrt(H)).astype(np.float32)
+    return W.float_to_bf16_bits(q), W.float_to_bf16_bits(K), w
+
+
+@pytest.mark.parametrize("mask_mode", [0, 1])
+@pytest.mark.parametrize("integer", [False, True])
+def test_brute_force_three_batches_rows_in_mixed_order(oracle, mask_mode, integer):
+    """Rows from every batch, listed in a shuffled order with repeated positions: each row must
+    be scored against its own batch's keys (a dropped or transposed batch offset picks another
+    batch's K, whose values differ)."""
+    rng = np.random.default_rng(21 + mask_mode)
+    B, S, H, D, m, k = 3, 40, 3, 8, 2, 6
+    T = S // m
+    qb, Kb, w = _rand_case_batched(rng, B, S, H, D, T, integer=integer)
+    bi, bs, _ = _brute(qb, Kb, w, m, k, mask_mode)
+    # whole problem through the all-rows driver
+    oi, os_ = oracle.topk_all(qb, Kb, w, m, k, mask_mode)
+    assert np.array_equal(oi, bi)
+    assert np.array_equal(os_, bs) if integer else np.allclose(os_, bs, rtol=1e-13, atol=1e-13)
+    # a shuffled list of (batch, position) pairs, some twice
+    n = 70
+    b_of = rng.integers(0, B, size=n).astype(np.int32)
+    t_of = rng.integers(0, S, size=n).astype(np.int64)
+    assert set(b_of) == {0, 1, 2}
+    ri, rs = oracle.topk_rows(qb[b_of, t_of], w[b_of, t_of], Kb, b_of, t_of, m, k, mask_mode)
+    assert np.array_equal(ri, bi[b_of, t_of])
+    assert np.array_equal(rs, bs[b_of, t_of]) if integer else np.allclose(rs, bs[b_of, t_of], rtol=1e-13, atol=1e-13)
+
+
+@pytest.mark.parametrize("n_threads", [2, 5, 16])
+def test_row_fan_out_over_threads_changes_nothing(oracle, n_threads):
+    """n_threads > 1 must return, bit for bit, what one thread returns, and that must be the
+    brute-force result: more threads than rows, a row count that does not divide, ties."""
+    rng = np.random.default_rng(23)
+    B, S, H, D, m, k = 2, 37, 4, 16, 3, 5
+    T = 12
+    for integer in (False, True):
+        qb, Kb, w = _rand_case_batched(rng, B, S, H, D, T, integer=integer)
+        bi, bs, _ = _brute(qb, Kb, w, m, k, 1)
+        for n in (1, 3, B * S):
+            sel = rng.permutation(B * S)[:n]
+            b_of = (sel // S).astype(np.int32)
+            t_of = (sel % S).astype(np.int64)
+            one = oracle.topk_rows(qb[b_of, t_of], w[b_of, t_of], Kb, b_of, t_of, m, k, 1, n_threads=1)
+            many = oracle.topk_rows(qb[b_of, t_of], w[b_of, t_of], Kb, b_of, t_of, m, k, 1,
+                                    n_threads=n_threads)
+            assert np.array_equal(one[0], many[0])
+            assert np.array_equal(one[1].view(np.int64), many[1].view(np.int64))
+            assert np.array_equal(many[0], bi[b_of, t_of])
+            if integer:
+                assert np.array_equal(many[1], bs[b_of, t_of])
+
+
+def test_score_at_listed_keys(oracle):
+    """Scores at a shuffled list of key indices (with repeats): equal to the materialized
+    einsum row at those indices, and a negative index gives NaN in exactly that place."""
+    rng = np.random.default_rng(24)
+    S, H, D, T = 5, 6, 16, 90
+    for integer in (False, True):
+        qb, Kb, w = _rand_case_batched(rng, 1, S, H, D, T, integer=integer)
+        _, _, full = _brute(qb, Kb, w, 1, 1, 0)  # [1, S, T] fp64 scores
+        for t in range(S):
+            idx = rng.integers(0, T, size=40).astype(np.int32)
+            idx[[3, 17, 39]] = -1
+            idx[5] = idx[6] = T - 1
+            idx[7] = 0
+            got = oracle.score_at(qb[0, t], Kb[0], w[0, t], idx)
+            hole = idx < 0
+            assert np.array_equal(np.isnan(got), hole)
+            ref = full[0, t, idx[~hole]]
+            if integer:
+                assert np.array_equal(got[~hole], ref)
+            else:
+                assert np.allclose(got[~hole], ref, rtol=1e-13, atol=1e-13)
+            # and bit-equal to the whole-row routine at the same places
+            assert np.array_equal(got[~hole], oracle.score_row(qb[0, t], Kb[0], w[0, t])[idx[~hole]])
+        assert oracle.score_at(qb[0, 0], Kb[0], w[0, 0], np.zeros(0, dtype=np.int32)).size == 0
+
+
 # ----------------------------------------------------------------------------- planted keys
 def test_planted_keys_are_the_top(oracle):
     wl = W.CONFIGS["tiny"]
@@ -372,3 +460,12 @@ def test_workload_table_matches_closed_forms():
         assert wl.legal_pairs() == wl.m * T * (T - 1) // 2 + T
     assert W.CONFIGS["tiny"].legal_pairs() == 1024 * 256
     assert W.CONFIGS["flash_4k"].flop_per_pair() == 16384
+
+
+def test_workload_pair_accounting_agrees_with_the_oracle_mask(oracle):
+    # the FLOP accounting of the benchmark counts legal pairs; it must count what the oracle masks
+    for wl in (W.CONFIGS["tiny"], W.CONFIGS["flash_4k"],
+               W.Workload("odd", B=2, S=103, H=4, D=32, m=3, k=5, mask_mode=W.MASK_CAUSAL_BLOCK)):
+        per_row = [oracle.legal_count(t, wl.T, wl.m, wl.mask_mode) for t in range(wl.S)]
+        assert per_row == [wl.legal_count(t) for t in range(wl.S)]
+        assert wl.legal_pairs() == wl.B * sum(per_row)
