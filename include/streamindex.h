@@ -127,6 +127,21 @@ si_status si_indexer_topk_fused(const void* q, const void* K, const float* w, co
                                 int32_t* out_idx, float* out_score, void* workspace,
                                 size_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate device memory or hand over a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the single-pass schedule of
+ * si_indexer_topk_fused with its scratch memory in a static array inside the library instead of
+ * a workspace argument.  Same arguments otherwise, same bits out.  Allocates nothing, frees
+ * nothing, enqueues kernel launches only.
+ *   Limits: k <= 1024 and S <= 64 * 131072 (SI_ERR_UNSUPPORTED_SHAPE beyond; nothing is launched).
+ *   The array is 39,846,144 bytes and exists once per GPU the library runs on, for the life of
+ *   the process.  Its device address is looked up on the first call on each device (make that
+ *   call outside stream capture).  Every call on a GPU uses that GPU's one array: calls that
+ *   overlap in time on the same GPU, from any stream or thread, race; the array keeps the last
+ *   call's contents and each call clears what it needs cleared (its launch counters) itself. */
+si_status si_indexer_topk_static(const void* q, const void* K, const float* w, const si_dims* dims,
+                                 int32_t m, int32_t k, si_mask_mode mask_mode, int32_t* out_idx,
+                                 float* out_score, void* stream);
+
 /* Step "score tile" alone (the fused score kernel of Section 5): fp32 scores of queries
  * [s0, s0+c_S) against keys [t0, t0+c_T) of every batch, ReLU and the weighted head sum
  * done in registers.  tile: device [B, c_S, c_T] f32, row stride c_T.  Entries whose query

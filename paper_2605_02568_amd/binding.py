@@ -24,7 +24,7 @@ PROFILE_CLASS_NAMES = ("score_tile", "filter_scores", "compact", "finalize", "in
 
 EXPORTS = (
     "si_plan_tiles", "si_workspace_bytes", "si_indexer_topk", "si_indexer_topk_tiled",
-    "si_fused_workspace_bytes", "si_indexer_topk_fused",
+    "si_fused_workspace_bytes", "si_indexer_topk_fused", "si_indexer_topk_static",
     "si_score_tile", "si_topk_from_scores", "si_materialize_bytes", "si_profile_enable",
     "si_profile_reset", "si_profile_read", "si_profile_phases", "si_wall_clock_khz", "si_strerror",
     "si_last_hip_error",
@@ -76,6 +76,9 @@ def load():
     L.si_indexer_topk_fused.argtypes = [c_void_p, c_void_p, c_void_p, POINTER(si_dims), c_int32,
                                         c_int32, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
                                         c_size_t, c_void_p]
+    L.si_indexer_topk_static.restype = c_int32
+    L.si_indexer_topk_static.argtypes = [c_void_p, c_void_p, c_void_p, POINTER(si_dims), c_int32,
+                                         c_int32, c_int32, c_void_p, c_void_p, c_void_p]
     L.si_score_tile.restype = c_int32
     L.si_score_tile.argtypes = [c_void_p, c_void_p, c_void_p, POINTER(si_dims), c_int32, c_int32,
                                 c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p]
@@ -199,6 +202,17 @@ def si_indexer_topk_fused(q, K, w, m, k, mask_mode, c_S, out_idx, out_score, wor
         _dev_ptr(out_idx, torch.int32, "out_idx"), _dev_ptr(out_score, torch.float32, "out_score"),
         _dev_ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
         _stream_handle(stream)), "si_indexer_topk_fused")
+
+
+def si_indexer_topk_static(q, K, w, m, k, mask_mode, out_idx, out_score, stream=None):
+    """No workspace argument: the library's static scratch array is used (k <= 1024)."""
+    dims = _dims_of(q, K, w)
+    _expect_out(out_idx, out_score, (dims.B, dims.S, k))
+    _check(load().si_indexer_topk_static(
+        _dev_ptr(q, torch.bfloat16, "q"), _dev_ptr(K, torch.bfloat16, "K"),
+        _dev_ptr(w, torch.float32, "w"), byref(dims), m, k, mask_mode,
+        _dev_ptr(out_idx, torch.int32, "out_idx"), _dev_ptr(out_score, torch.float32, "out_score"),
+        _stream_handle(stream)), "si_indexer_topk_static")
 
 
 def si_score_tile(q, K, w, m, mask_mode, s0, t0, c_S, c_T, tile, stream=None):

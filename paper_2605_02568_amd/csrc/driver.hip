@@ -13,6 +13,21 @@
 
 #include "si_internal.h"
 
+// Scratch of si_indexer_topk_static, the entry point that allocates nothing: the workspace of the
+// single-pass schedule for k <= kStaticMaxK (launch counters, then 256 x 8 row buffers of
+// 2k + 384 keys), as one static array in device memory.  Each GPU the library runs on holds its
+// own copy from the moment the code object is loaded until the process ends.  In host code the
+// name `scratch` is only a handle: the address kernels can use comes from hipGetSymbolAddress,
+// once per device (static_scratch below), and only that pointer is ever passed on.
+namespace {
+constexpr int kStaticMaxK = 1024;
+constexpr int kStaticMaxLaunches = 64;  // counters: one 256-byte block
+constexpr size_t kStaticScratchBytes =
+    256 + static_cast<size_t>(si::kFusedSlots) * si::kQueriesPerBlock *
+              (si::kFusedTriggerMul * kStaticMaxK + si::kFusedRowSlack) * sizeof(si::key64_t);
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace si {
 
 namespace {
@@ -149,6 +164,7 @@ FusedLayout carve_fused(void* base, int64_t S, int64_t k, int64_t c_S) {
 // Immutable facts about a device, looked up once per device and process.
 struct DeviceInfo {
     std::atomic<int> compute_units{0};
+    std::atomic<void*> static_scratch{nullptr};  // this device's copy of `scratch`
 };
 constexpr int kMaxDevices = 64;
 DeviceInfo g_device[kMaxDevices];
@@ -168,6 +184,24 @@ hipError_t fused_workgroups(int32_t* n) {
         if (dev >= 0 && dev < kMaxDevices) g_device[dev].compute_units.store(cus, std::memory_order_release);
     }
     *n = std::min<int32_t>(cus, kFusedSlots);
+    return hipSuccess;
+}
+
+// Device address of the current device's copy of `scratch`: asked from the runtime on the first
+// call on that device (with that device current), remembered afterwards.
+hipError_t static_scratch(void** ptr) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const bool tracked = dev >= 0 && dev < kMaxDevices;
+    void* p = tracked ? g_device[dev].static_scratch.load(std::memory_order_acquire) : nullptr;
+    if (p == nullptr) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        if (tracked) g_device[dev].static_scratch.store(p, std::memory_order_release);
+    }
+    *ptr = p;
     return hipSuccess;
 }
 
@@ -371,6 +405,25 @@ si_status si_indexer_topk_fused(const void* q, const void* K, const float* w, co
     c_S = fused_rows_per_launch(c_S, dims->S);
     const FusedLayout L = carve_fused(workspace, dims->S, k, c_S);
     if (L.bytes > workspace_bytes) return SI_ERR_WORKSPACE_TOO_SMALL;
+    return run_fused(q, K, w, *dims, m, k, mask_mode, c_S, L, out_idx, out_score,
+                     static_cast<hipStream_t>(stream));
+}
+
+si_status si_indexer_topk_static(const void* q, const void* K, const float* w, const si_dims* dims,
+                                 int32_t m, int32_t k, si_mask_mode mask_mode, int32_t* out_idx,
+                                 float* out_score, void* stream) {
+    si_status st = check_dims(dims, m, k, mask_mode);
+    if (st != SI_OK) return st;
+    if (!q || !K || !w || !out_idx || !out_score) return SI_ERR_INVALID_ARG;
+    // beyond what the static array was sized for: refuse, never spill over
+    if (k > kStaticMaxK) return SI_ERR_UNSUPPORTED_SHAPE;
+    const int32_t c_S = fused_rows_per_launch(0, dims->S);
+    if ((static_cast<int64_t>(dims->S) + c_S - 1) / c_S > kStaticMaxLaunches) return SI_ERR_UNSUPPORTED_SHAPE;
+    void* base = nullptr;
+    hipError_t e = static_scratch(&base);
+    if (e != hipSuccess) return hip_fail(e);
+    const FusedLayout L = carve_fused(base, dims->S, k, c_S);
+    if (L.bytes > kStaticScratchBytes) return SI_ERR_UNSUPPORTED_SHAPE;  // (cannot happen within the two limits)
     return run_fused(q, K, w, *dims, m, k, mask_mode, c_S, L, out_idx, out_score,
                      static_cast<hipStream_t>(stream));
 }

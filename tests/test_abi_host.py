@@ -131,6 +131,21 @@ def test_single_pass_workspace_and_argument_checks():
                                None) == P.SI_ERR_INVALID_ARG
 
 
+def test_static_scratch_entry_point_rejects_on_the_host():
+    """si_indexer_topk_static: what its static array cannot hold is refused before any GPU call."""
+    lib = P.load()
+    fake = ctypes.c_void_p(256)
+    d = binding.si_dims(1, 64, 4, 32, 16)
+    call = lambda dims, k, q=fake: lib.si_indexer_topk_static(  # noqa: E731
+        q, fake, fake, ctypes.byref(dims), 4, k, 1, fake, fake, None)
+    assert call(d, 1025) == P.SI_ERR_UNSUPPORTED_SHAPE
+    assert call(d, 0) == P.SI_ERR_INVALID_ARG
+    assert call(d, 8, q=None) == P.SI_ERR_INVALID_ARG
+    assert call(binding.si_dims(1, 64, 4, 48, 16), 8) == P.SI_ERR_UNSUPPORTED_SHAPE
+    too_long = binding.si_dims(1, 64 * 131072 + 1, 4, 32, 16)  # more launches than it has counters for
+    assert call(too_long, 8) == P.SI_ERR_UNSUPPORTED_SHAPE
+
+
 def test_product_package_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2605_02568_amd")
     for dirpath, _, files in os.walk(pkg):
