@@ -55,15 +55,68 @@ def _phase_budget(P, words, steps, kernel_ms_per_step):
         return {"error": "the instrumented kernel did not run (head shape or k outside its range)"}
     to_ms = 1.0 / rate_khz / steps
     out = {"wall_clock_khz": int(rate_khz), "workgroups": int(len(used)), "kernel_ms_per_step": kernel_ms_per_step}
+    # which workgroups shared a compute unit (narrow shape: two per unit)
+    hw, xcc = used[:, names.index("hw_id")], used[:, names.index("xcc_id")]
+    unit = (xcc & 0xF) * 1024 + ((hw >> 13) & 7) * 32 + ((hw >> 12) & 1) * 16 + ((hw >> 8) & 0xF)
+    ids = [int(i) for i in range(len(words)) if words[i, names.index("launches")] > 0]
+    by_unit = {}
+    for wg, u in zip(ids, unit):
+        by_unit.setdefault(int(u), []).append(wg)
+    sizes = sorted(len(v) for v in by_unit.values())
+    out["compute_units_used"] = len(by_unit)
+    out["workgroups_per_unit_min_max"] = [sizes[0], sizes[-1]]
+    pairs = [v for v in by_unit.values() if len(v) == 2]
+    out["pairs_split_across_grid_halves"] = sum(1 for a, b in pairs if (a < len(ids) // 2) != (b < len(ids) // 2))
+    out["pairs_total"] = len(pairs)
+    out["example_units"] = [by_unit[u] for u in sorted(by_unit)[:6]]
     for i, name in enumerate(names):
+        if name in ("hw_id", "xcc_id", "start_tick"):
+            continue
         col = used[:, i].astype("float64")
-        if i <= names.index("resident"):
+        if i in P.PHASE_TIME_WORDS:
             out[name] = {"mean_ms": float(col.mean() * to_ms), "max_ms": float(col.max() * to_ms),
                          "share_of_kernel": float(col.mean() * to_ms / kernel_ms_per_step)}
         else:
             out[name] = {"mean": float(col.mean() / steps), "max": float(col.max() / steps)}
     out["ramp_and_tail_ms"] = kernel_ms_per_step - out["resident"]["mean_ms"]
     return out
+
+
+def _pair_overlap(log_words, n_events, rate_khz):
+    """From the phase-change logs of two workgroups (in the narrow shape: the two that share compute
+    unit 0's slot): over the time both were running, the share of time in which 0, 1 or 2 of them
+    were inside a key sweep.  Uses the events of the last launch only (the log is overwritten)."""
+    import numpy as np
+
+    def intervals(words):
+        ev = [(int(w) >> 4, int(w) & 15) for w in words if int(w) != 0]
+        ev.sort()
+        return ev  # (tick at which a phase ended, which phase)
+
+    a, b = intervals(log_words[:n_events]), intervals(log_words[n_events:2 * n_events])
+    if len(a) < 4 or len(b) < 4:
+        return None
+    t0, t1 = max(a[0][0], b[0][0]), min(a[-1][0], b[-1][0])
+    if t1 <= t0:
+        return None
+
+    def sweeping(ev, t):  # phase 1 = sweep: the interval ending at an event of phase 1
+        import bisect
+        i = bisect.bisect_right([e[0] for e in ev], t)
+        return i < len(ev) and ev[i][1] == 1
+
+    ticks = np.linspace(t0, t1, 4000)
+    ta, tb = [e[0] for e in a], [e[0] for e in b]
+    import bisect
+    counts = [0, 0, 0]
+    for t in ticks:
+        ia, ib = bisect.bisect_right(ta, t), bisect.bisect_right(tb, t)
+        n = int(ia < len(a) and a[ia][1] == 1) + int(ib < len(b) and b[ib][1] == 1)
+        counts[n] += 1
+    tot = float(sum(counts))
+    return {"window_ms": (t1 - t0) / rate_khz, "events": [len(a), len(b)],
+            "share_none_sweeping": counts[0] / tot, "share_one_sweeping": counts[1] / tot,
+            "share_both_sweeping": counts[2] / tot}
 
 
 def main() -> int:
@@ -76,6 +129,8 @@ def main() -> int:
     ap.add_argument("--schedule", choices=["auto", "fused", "tiled"], default="auto",
                     help="fused: single-pass kernel (k <= 2048); tiled: one launch per (c_S x c_T) "
                          "tile; auto: what si_indexer_topk picks (fused when it applies)")
+    ap.add_argument("--shape", type=int, choices=[0, 4, 8], default=0,
+                    help="single-pass schedule: queries per workgroup (8 wide, 4 narrow, 0 = the library's choice)")
     ap.add_argument("--c-s", type=int, default=0, help="explicit query tile (0 = planned)")
     ap.add_argument("--c-t", type=int, default=0, help="explicit key tile (0 = planned)")
     ap.add_argument("--oracle-rows", type=int, default=256,
@@ -137,8 +192,8 @@ def main() -> int:
 
     def step():
         if fused:
-            P.si_indexer_topk_fused(q, K, w, wl.m, wl.k, wl.mask_mode, c_S, out_idx, out_score, ws,
-                                    stream=stream)
+            P.si_indexer_topk_fused_shape(q, K, w, wl.m, wl.k, wl.mask_mode, c_S, args.shape, out_idx,
+                                          out_score, ws, stream=stream)
         else:
             P.si_indexer_topk_tiled(q, K, w, wl.m, wl.k, wl.mask_mode, c_S, c_T, out_idx, out_score, ws,
                                     stream=stream)
@@ -154,8 +209,9 @@ def main() -> int:
         if not fused:
             print("bench.py: --phases needs the single-pass schedule", file=sys.stderr)
             return 2
-        phase_words = torch.zeros(max(n_cu, 256) * P.PHASE_WORDS, dtype=torch.int64, device=dev)
-        P.si_profile_phases(phase_words, max(n_cu, 256))
+        phase_words = torch.zeros(2 * max(n_cu, 256) * P.PHASE_WORDS + 2 * P.PHASE_TRACE_EVENTS,
+                                  dtype=torch.int64, device=dev)
+        P.si_profile_phases(phase_words, 2 * max(n_cu, 256))
 
     # timed region: exactly `steps` steps, per-kernel HIP events recorded on the same stream
     P.si_profile_reset()
@@ -176,8 +232,14 @@ def main() -> int:
     phase_budget = None
     if phase_words is not None:
         P.si_profile_phases(None)
-        phase_budget = _phase_budget(P, phase_words.cpu().numpy().reshape(-1, P.PHASE_WORDS), args.steps,
-                                     prof["fused"][0] / args.steps)
+        host_words = phase_words.cpu().numpy()
+        n_slots = 2 * max(n_cu, 256)
+        phase_budget = _phase_budget(P, host_words[:n_slots * P.PHASE_WORDS].reshape(-1, P.PHASE_WORDS), args.steps,
+                                     (prof["fused"][0] + prof["fused_narrow"][0]) / args.steps)
+        n_wg = phase_budget.get("workgroups", 0)
+        if n_wg:
+            phase_budget["pair_overlap"] = _pair_overlap(host_words[n_slots * P.PHASE_WORDS:], P.PHASE_TRACE_EVENTS,
+                                                         phase_budget["wall_clock_khz"])
 
     if args.calibration_mib > 0:
         src = torch.ones(args.calibration_mib << 18, dtype=torch.float32, device=dev)
@@ -193,7 +255,13 @@ def main() -> int:
     flop_per_step = legal_pairs * wl.flop_per_pair()
     tflops = flop_per_step / sec_per_step / 1e12
 
-    score_ms, score_launches = prof["fused" if fused else "score_tile"]
+    if fused:  # whichever workgroup shape ran
+        score_ms = prof["fused"][0] + prof["fused_narrow"][0]
+        score_launches = prof["fused"][1] + prof["fused_narrow"][1]
+        shape_ran = 4 if prof["fused_narrow"][1] else 8
+    else:
+        score_ms, score_launches = prof["score_tile"]
+        shape_ran = 0
     score_ms_per_launch = score_ms / max(1, score_launches)
     flop_per_launch = flop_per_step * args.steps / max(1, score_launches)
     achieved = flop_per_launch / (score_ms_per_launch * 1e-3) / 1e12 if score_ms > 0 else 0.0
@@ -219,7 +287,7 @@ def main() -> int:
         "config": {
             "workload": wl.name, "B": wl.B, "S": wl.S, "H_I": wl.H, "D": wl.D, "T": T, "m": wl.m,
             "k": wl.k, "mask": "causal_block" if wl.mask_mode else "none",
-            "schedule": "fused" if fused else "tiled",
+            "schedule": "fused" if fused else "tiled", "queries_per_workgroup": shape_ran,
             "c_S": c_S, "c_T": c_T,
             "seed": wl.seed, "sigma_w": info["sigma_w"],
         },

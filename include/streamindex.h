@@ -121,7 +121,18 @@ si_status si_indexer_topk_tiled(const void* q, const void* K, const float* w,
  * c_S = queries per kernel launch (<= 0: the library's default, 131072; values above S are
  * clamped).  The split only resynchronises the workgroups' walk over the keys; it does not
  * change the result. */
+/* The kernel comes in two workgroup shapes that give the same bits: wide (8 queries per
+ * workgroup, one workgroup per compute unit: every staged key chunk serves 8 queries) and narrow
+ * (4 queries per workgroup, two workgroups per compute unit: while one of them merges, sorts or
+ * writes out, the other one's sweep keeps the matrix pipe busy).  si_indexer_topk_fused picks the
+ * narrow shape when the longest key range of a query is short (si_fused_shape_for tells which);
+ * si_indexer_topk_fused_shape takes queries_per_workgroup = 8, 4 or 0 (= that choice). */
 size_t si_fused_workspace_bytes(const si_dims* dims, int32_t k, int32_t c_S);
+int32_t si_fused_shape_for(const si_dims* dims, int32_t m, int32_t k, si_mask_mode mask_mode);
+si_status si_indexer_topk_fused_shape(const void* q, const void* K, const float* w, const si_dims* dims,
+                                      int32_t m, int32_t k, si_mask_mode mask_mode, int32_t c_S,
+                                      int32_t queries_per_workgroup, int32_t* out_idx, float* out_score,
+                                      void* workspace, size_t workspace_bytes, void* stream);
 si_status si_indexer_topk_fused(const void* q, const void* K, const float* w, const si_dims* dims,
                                 int32_t m, int32_t k, si_mask_mode mask_mode, int32_t c_S,
                                 int32_t* out_idx, float* out_score, void* workspace,
@@ -172,9 +183,9 @@ uint64_t si_materialize_bytes(const si_dims* dims);
  * those events and returns, per kernel class, the summed duration in milliseconds and the
  * number of launches since the last reset.  Classes: 0 score tile (with its fused filter),
  * 1 filter of caller-supplied scores, 2 compaction (select + merge), 3 final sort + write-out,
- * 4 buffer / counter init, 5 single-pass kernel.  One set of totals per process: meant for a
+ * 4 buffer / counter init, 5 single-pass kernel (wide shape), 6 single-pass kernel (narrow shape).  One set of totals per process: meant for a
  * single benchmarking thread (concurrent callers are serialised, their launches are summed). */
-#define SI_PROFILE_CLASSES 6
+#define SI_PROFILE_CLASSES 7
 si_status si_profile_enable(int32_t on);
 si_status si_profile_reset(void);
 si_status si_profile_read(double* ms_per_class, int64_t* launches_per_class);
@@ -182,13 +193,21 @@ si_status si_profile_read(double* ms_per_class, int64_t* launches_per_class);
 /* Phase clock of the single-pass kernel, for the phase budget of a benchmark run.  While
  * device_words is non-NULL, launches of the single-pass schedule with D = 128, 33..64 heads and
  * k <= 1024 run an instrumented copy of the kernel in which workgroup j ADDS to
- * device_words[j*16 + i] (uint64, device memory, at least n_workgroups*16 words, n_workgroups >=
- * the device's compute units, cleared by the caller):
+ * device_words[j*32 + i] (uint64, device memory, at least n_workgroups*32 + 4096 words,
+ * n_workgroups >= twice the device's compute units, cleared by the caller):
  *   i = 0..5  time in ticks of the device's constant wall clock (hipDeviceAttributeWallClockRate):
  *             0 item set-up and barriers around sweeps, 1 key sweeps, 2 in-kernel merges,
  *             3 final cut + sort + write-out, 4 barrier behind the write-out, 5 residency
  *             (first instruction to exit, summed over launches);
- *   i = 6..10 counts: 6 work items, 7 sweep calls, 8 128-key steps, 9 merges, 10 launches.
+ *   i = 6..10 counts: 6 work items, 7 sweep calls, 8 128-key steps, 9 merges, 10 launches;
+ *   i = 11..14 parts of 2 (barrier + next chunks requested, row read, radix descent, write-back +
+ *             barrier); i = 15..19 parts of 3 (row read, exact cut, keys to LDS, sort, write-out).
+ *             The instrumented kernel waits for outstanding memory operations at these marks.
+ *   i = 20, 21 set, not added: hardware id and XCC id registers of the workgroup's first wave
+ *             (which compute unit it ran on); i = 22: tick of its first instruction.
+ *   Behind the n_workgroups blocks of words: two logs of 2048 words, (tick << 4) | phase
+ *   that ended (0..4), written by workgroup 0 and by the first workgroup of the grid's second half
+ *   (in the narrow shape these two share a compute unit); unused entries stay as the caller left them.
  * Results are unchanged.  Pass NULL to switch back to the plain kernel.  The pointer is global to
  * the process: meant for one benchmarking thread. */
 si_status si_profile_phases(uint64_t* device_words, int32_t n_workgroups);

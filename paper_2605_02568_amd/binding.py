@@ -19,12 +19,13 @@ SI_ERR_WORKSPACE_TOO_SMALL = -3
 SI_ERR_HIP = -4
 SI_MASK_NONE = 0
 SI_MASK_CAUSAL_BLOCK = 1
-SI_PROFILE_CLASSES = 6
-PROFILE_CLASS_NAMES = ("score_tile", "filter_scores", "compact", "finalize", "init", "fused")
+SI_PROFILE_CLASSES = 7
+PROFILE_CLASS_NAMES = ("score_tile", "filter_scores", "compact", "finalize", "init", "fused", "fused_narrow")
 
 EXPORTS = (
     "si_plan_tiles", "si_workspace_bytes", "si_indexer_topk", "si_indexer_topk_tiled",
-    "si_fused_workspace_bytes", "si_indexer_topk_fused", "si_indexer_topk_static",
+    "si_fused_workspace_bytes", "si_indexer_topk_fused", "si_indexer_topk_fused_shape",
+    "si_fused_shape_for", "si_indexer_topk_static",
     "si_score_tile", "si_topk_from_scores", "si_materialize_bytes", "si_profile_enable",
     "si_profile_reset", "si_profile_read", "si_profile_phases", "si_wall_clock_khz", "si_strerror",
     "si_last_hip_error",
@@ -76,6 +77,12 @@ def load():
     L.si_indexer_topk_fused.argtypes = [c_void_p, c_void_p, c_void_p, POINTER(si_dims), c_int32,
                                         c_int32, c_int32, c_int32, c_void_p, c_void_p, c_void_p,
                                         c_size_t, c_void_p]
+    L.si_indexer_topk_fused_shape.restype = c_int32
+    L.si_indexer_topk_fused_shape.argtypes = [c_void_p, c_void_p, c_void_p, POINTER(si_dims), c_int32,
+                                              c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p,
+                                              c_void_p, c_size_t, c_void_p]
+    L.si_fused_shape_for.restype = c_int32
+    L.si_fused_shape_for.argtypes = [POINTER(si_dims), c_int32, c_int32, c_int32]
     L.si_indexer_topk_static.restype = c_int32
     L.si_indexer_topk_static.argtypes = [c_void_p, c_void_p, c_void_p, POINTER(si_dims), c_int32,
                                          c_int32, c_int32, c_void_p, c_void_p, c_void_p]
@@ -204,6 +211,23 @@ def si_indexer_topk_fused(q, K, w, m, k, mask_mode, c_S, out_idx, out_score, wor
         _stream_handle(stream)), "si_indexer_topk_fused")
 
 
+def si_fused_shape_for(B, S, H_I, D, T, m, k, mask_mode) -> int:
+    """Queries per workgroup (8 or 4) si_indexer_topk_fused picks for this problem; 0 = not applicable."""
+    return int(load().si_fused_shape_for(byref(si_dims(B, S, H_I, D, T)), m, k, mask_mode))
+
+
+def si_indexer_topk_fused_shape(q, K, w, m, k, mask_mode, c_S, queries_per_workgroup, out_idx, out_score,
+                                workspace, stream=None):
+    dims = _dims_of(q, K, w)
+    _expect_out(out_idx, out_score, (dims.B, dims.S, k))
+    _check(load().si_indexer_topk_fused_shape(
+        _dev_ptr(q, torch.bfloat16, "q"), _dev_ptr(K, torch.bfloat16, "K"),
+        _dev_ptr(w, torch.float32, "w"), byref(dims), m, k, mask_mode, c_S, queries_per_workgroup,
+        _dev_ptr(out_idx, torch.int32, "out_idx"), _dev_ptr(out_score, torch.float32, "out_score"),
+        _dev_ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
+        _stream_handle(stream)), "si_indexer_topk_fused_shape")
+
+
 def si_indexer_topk_static(q, K, w, m, k, mask_mode, out_idx, out_score, stream=None):
     """No workspace argument: the library's static scratch array is used (k <= 1024)."""
     dims = _dims_of(q, K, w)
@@ -255,9 +279,14 @@ def si_profile_reset():
     _check(load().si_profile_reset(), "si_profile_reset")
 
 
-PHASE_WORDS = 16
+PHASE_WORDS = 32
+PHASE_TRACE_EVENTS = 2048
 PHASE_NAMES = ("setup", "sweep", "merge", "final", "final_wait", "resident",
-               "items", "sweeps", "steps", "merges", "launches")
+               "items", "sweeps", "steps", "merges", "launches",
+               "merge_sync", "merge_load", "merge_radix", "merge_keep",
+               "final_load", "final_radix", "final_keep", "final_sort", "final_write",
+               "hw_id", "xcc_id", "start_tick")
+PHASE_TIME_WORDS = (0, 1, 2, 3, 4, 5, 11, 12, 13, 14, 15, 16, 17, 18, 19)
 
 
 def si_profile_phases(device_words, n_workgroups: int = 0):
@@ -265,8 +294,8 @@ def si_profile_phases(device_words, n_workgroups: int = 0):
     if device_words is None:
         _check(load().si_profile_phases(None, 0), "si_profile_phases")
         return
-    if device_words.numel() < n_workgroups * PHASE_WORDS:
-        raise ValueError("device_words must hold n_workgroups * 16 words")
+    if device_words.numel() < n_workgroups * PHASE_WORDS + 2 * PHASE_TRACE_EVENTS:
+        raise ValueError("device_words must hold n_workgroups * 32 + 4096 words")
     _check(load().si_profile_phases(_dev_ptr(device_words, torch.int64, "device_words"), n_workgroups),
            "si_profile_phases")
 

@@ -169,10 +169,10 @@ struct DeviceInfo {
 constexpr int kMaxDevices = 64;
 DeviceInfo g_device[kMaxDevices];
 
-// Workgroups the single-pass kernel is launched with: one per compute unit of the current
-// device (each holds 8 waves at 2 per SIMD and 100+ KB of LDS), at most kFusedSlots (what the
-// workspace has row buffers for).
-hipError_t fused_workgroups(int32_t* n) {
+// Workgroups the single-pass kernel is launched with: one wide (8-wave) or two narrow (4-wave)
+// workgroups per compute unit of the current device -- either way 2 waves per SIMD, which is what
+// their register budget allows -- and at most what the workspace has row buffers for.
+hipError_t fused_workgroups(int32_t waves, int32_t* n) {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
@@ -183,8 +183,24 @@ hipError_t fused_workgroups(int32_t* n) {
         if (cus < 1) return hipErrorInvalidDevice;
         if (dev >= 0 && dev < kMaxDevices) g_device[dev].compute_units.store(cus, std::memory_order_release);
     }
-    *n = std::min<int32_t>(cus, kFusedSlots);
+    const int32_t per_cu = kQueriesPerBlock / waves;
+    *n = std::min<int32_t>(cus * per_cu, kFusedSlots * per_cu);
     return hipSuccess;
+}
+
+// Workgroup shape of the single-pass schedule when the caller does not choose (see SweepShape in
+// score_sweep.h).  Per work item the merges, the final cut + sort and the write-out cost a time
+// that depends on k but not on the item's key range, with the matrix pipe idle; two narrow
+// workgroups per compute unit overlap one's such phases with the other's sweep, at the price of
+// staging every key chunk for 4 queries instead of 8 and of a lone sweeping wave per SIMD that
+// cannot hide its own stalls.  Measured on MI355X at the V4 head shape (S = 4 T, causal, k = 512
+// and 1024): the narrow shape is 5-6 % faster at 8,192 keys per query, 1 % at 16,384, even at
+// 32,768 and 3 % slower at 262,144.
+constexpr int64_t kNarrowMaxKeys = 16384;
+int32_t fused_shape_for(const si_dims& d, int32_t m, int32_t mask_mode) {
+    int64_t longest = d.T;  // keys of the longest row
+    if (mask_mode == SI_MASK_CAUSAL_BLOCK) longest = std::min<int64_t>(d.T, static_cast<int64_t>(d.S) / m);
+    return longest <= kNarrowMaxKeys ? 4 : 8;
 }
 
 // Device address of the current device's copy of `scratch`: asked from the runtime on the first
@@ -208,10 +224,11 @@ hipError_t static_scratch(void** ptr) {
 // The single-pass schedule on a carved workspace: one counter-clearing kernel, then one launch
 // per c_S queries.  Arguments have been checked.
 si_status run_fused(const void* q, const void* K, const float* w, const si_dims& d, int32_t m, int32_t k,
-                    int32_t mask_mode, int32_t c_S, const FusedLayout& L, int32_t* out_idx,
+                    int32_t mask_mode, int32_t c_S, int32_t waves, const FusedLayout& L, int32_t* out_idx,
                     float* out_score, hipStream_t hs) {
+    if (waves == 0) waves = fused_shape_for(d, m, mask_mode);
     int32_t n_wg = 0;
-    hipError_t e = fused_workgroups(&n_wg);
+    hipError_t e = fused_workgroups(waves, &n_wg);
     if (e != hipSuccess) return hip_fail(e);
     e = timed(kProfInit, hs, [&] {
         return launch_zero_ints(L.counters, static_cast<int32_t>(L.n_launches), hs);
@@ -220,12 +237,13 @@ si_status run_fused(const void* q, const void* K, const float* w, const si_dims&
     int64_t launch = 0;
     for (int64_t s0 = 0; s0 < d.S; s0 += c_S, ++launch) {
         const int32_t rows = static_cast<int32_t>(std::min<int64_t>(c_S, d.S - s0));
-        e = timed(kProfFused, hs, [&] {
+        e = timed(waves == 8 ? kProfFused : kProfFusedNarrow, hs, [&] {
             // (timed holds the profiler's lock: the phase clock's buffer is read under it)
             unsigned long long* phase = g_prof.phase_slots >= n_wg ? g_prof.phase : nullptr;
             if (phase != nullptr && !(d.D == 128 && d.H_I > 32 && k <= 1024)) phase = nullptr;
             return launch_fused(q, K, w, d, m, mask_mode, k, static_cast<int32_t>(s0), rows, L.slots,
-                                n_wg, L.counters + launch, out_idx, out_score, phase, hs);
+                                waves, n_wg, L.counters + launch, out_idx, out_score, phase,
+                                g_prof.phase_slots, hs);
         });
         if (e != hipSuccess) return hip_fail(e);
     }
@@ -393,20 +411,35 @@ size_t si_fused_workspace_bytes(const si_dims* dims, int32_t k, int32_t c_S) {
     return carve_fused(nullptr, dims->S, k, c_S).bytes;
 }
 
-si_status si_indexer_topk_fused(const void* q, const void* K, const float* w, const si_dims* dims,
-                                int32_t m, int32_t k, si_mask_mode mask_mode, int32_t c_S,
-                                int32_t* out_idx, float* out_score, void* workspace,
-                                size_t workspace_bytes, void* stream) {
+si_status si_indexer_topk_fused_shape(const void* q, const void* K, const float* w, const si_dims* dims,
+                                      int32_t m, int32_t k, si_mask_mode mask_mode, int32_t c_S,
+                                      int32_t queries_per_workgroup, int32_t* out_idx, float* out_score,
+                                      void* workspace, size_t workspace_bytes, void* stream) {
     si_status st = check_dims(dims, m, k, mask_mode);
     if (st != SI_OK) return st;
     if (k > kFusedMaxK) return SI_ERR_UNSUPPORTED_SHAPE;
     if (!q || !K || !w || !out_idx || !out_score || !workspace) return SI_ERR_INVALID_ARG;
+    if (queries_per_workgroup != 0 && queries_per_workgroup != 4 && queries_per_workgroup != 8)
+        return SI_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return SI_ERR_INVALID_ARG;
     c_S = fused_rows_per_launch(c_S, dims->S);
     const FusedLayout L = carve_fused(workspace, dims->S, k, c_S);
     if (L.bytes > workspace_bytes) return SI_ERR_WORKSPACE_TOO_SMALL;
-    return run_fused(q, K, w, *dims, m, k, mask_mode, c_S, L, out_idx, out_score,
+    return run_fused(q, K, w, *dims, m, k, mask_mode, c_S, queries_per_workgroup, L, out_idx, out_score,
                      static_cast<hipStream_t>(stream));
+}
+
+si_status si_indexer_topk_fused(const void* q, const void* K, const float* w, const si_dims* dims,
+                                int32_t m, int32_t k, si_mask_mode mask_mode, int32_t c_S,
+                                int32_t* out_idx, float* out_score, void* workspace,
+                                size_t workspace_bytes, void* stream) {
+    return si_indexer_topk_fused_shape(q, K, w, dims, m, k, mask_mode, c_S, 0, out_idx, out_score,
+                                       workspace, workspace_bytes, stream);
+}
+
+int32_t si_fused_shape_for(const si_dims* dims, int32_t m, int32_t k, si_mask_mode mask_mode) {
+    if (check_dims(dims, m, k, mask_mode) != SI_OK || k > kFusedMaxK) return 0;
+    return fused_shape_for(*dims, m, mask_mode);
 }
 
 si_status si_indexer_topk_static(const void* q, const void* K, const float* w, const si_dims* dims,
@@ -424,7 +457,7 @@ si_status si_indexer_topk_static(const void* q, const void* K, const float* w, c
     if (e != hipSuccess) return hip_fail(e);
     const FusedLayout L = carve_fused(base, dims->S, k, c_S);
     if (L.bytes > kStaticScratchBytes) return SI_ERR_UNSUPPORTED_SHAPE;  // (cannot happen within the two limits)
-    return run_fused(q, K, w, *dims, m, k, mask_mode, c_S, L, out_idx, out_score,
+    return run_fused(q, K, w, *dims, m, k, mask_mode, c_S, 0, L, out_idx, out_score,
                      static_cast<hipStream_t>(stream));
 }
 

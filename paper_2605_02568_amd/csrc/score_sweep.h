@@ -38,15 +38,27 @@ namespace si {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int kWaves = 8;            // waves per workgroup, one query each
+constexpr int kWaves = 8;            // waves per workgroup of the wide shape, one query each
 constexpr int kQB = kWaves;          // queries per workgroup
 constexpr int kKeyChunk = 128;       // keys per LDS buffer
 constexpr int kScoreThreads = 64 * kWaves;
 constexpr int kLdsBuffers = 3;
 
+// Two workgroup shapes share the sweep.
+//   wide   (8 waves): 8 queries share every staged key chunk; chunks of 128 keys in a ring of three
+//          buffers (96 KiB at D = 128), one workgroup per compute unit.  Least key traffic per
+//          query: the shape for long key ranges and for the tiled schedule.
+//   narrow (4 waves): 4 queries per workgroup, chunks of 64 keys in a ring of four buffers (64 KiB),
+//          so that TWO workgroups fit a compute unit, each SIMD holding one wave of each.  While one
+//          of them merges, sorts or writes out (no matrix work), the other one's sweep keeps the
+//          matrix pipe busy: the shape for short key ranges, where those phases are a large share.
+template <int WAVES> struct SweepShape;
+template <> struct SweepShape<8> { static constexpr int kChunk = 128, kBuffers = 3; };
+template <> struct SweepShape<4> { static constexpr int kChunk = 64, kBuffers = 4; };
+
 // LDS bytes the sweep needs for head dimension D (1 KiB aligned).
-template <int D>
-constexpr int sweep_lds_bytes() { return kLdsBuffers * kKeyChunk * D * 2; }
+template <int D, int WAVES = kWaves>
+constexpr int sweep_lds_bytes() { return SweepShape<WAVES>::kBuffers * SweepShape<WAVES>::kChunk * D * 2; }
 
 // max(x, 0) on the bit pattern: negative floats (and -0) are negative integers.
 __device__ inline float relu(float x) { return __int_as_float(max(__float_as_int(x), 0)); }
@@ -139,24 +151,23 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t chunk_rsrc(const __bf16* Kb, i
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base), 0, static_cast<int>(remain), 0x00020000);
 }
 
-// Starts the trip of the first two 128-key chunks of a sweep over Kb into LDS buffers 0 and 1
-// (the same transfers the sweep's own prologue would issue).  A sweep called with
-// PREFETCHED = true expects them in flight or landed and skips its own.  All 8 waves call it.
-template <int D>
+// Starts the trip of the first chunks of a sweep over Kb (all but one buffer of the ring: two
+// 128-key chunks in the wide shape, three 64-key chunks in the narrow one) into LDS buffers 0, 1, ...
+// -- the same transfers the sweep's own prologue would issue.  A sweep called with
+// PREFETCHED = true expects them in flight or landed and skips its own.  All waves call it.
+template <int D, int WAVES = kWaves>
 __device__ __forceinline__ void sweep_prefetch(unsigned char* lds, const __bf16* __restrict__ Kb,
                                                int key_clamp) {
 #if defined(__HIP_DEVICE_COMPILE__)
-    constexpr int kRowBytes = D * 2;
-    constexpr int kPieces = D / 8;
-    constexpr int kBufBytes = kKeyChunk * kRowBytes;
-    constexpr int kRowsPerLoad = 64 / kPieces;
-    constexpr int kLoads = kKeyChunk / kRowsPerLoad / kWaves;
+    constexpr int kChunk = SweepShape<WAVES>::kChunk;
+    constexpr int kBufBytes = kChunk * D * 2;
+    constexpr int kLoads = kBufBytes / 1024 / WAVES;
     typedef __attribute__((address_space(3))) void lds_void;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
-        const __amdgpu_buffer_rsrc_t krsrc = chunk_rsrc<D>(Kb, key_clamp, c * kKeyChunk);
+    for (int c = 0; c < SweepShape<WAVES>::kBuffers - 1; ++c) {
+        const __amdgpu_buffer_rsrc_t krsrc = chunk_rsrc<D>(Kb, key_clamp, c * kChunk);
 #pragma unroll
         for (int i = 0; i < kLoads; ++i) {
             const int blk = wave * kLoads + i;
@@ -201,7 +212,7 @@ struct SweepOut {
 // Returns the number of keys swept (a multiple of 128, or >= n_keys at the natural end).  On
 // return every global -> LDS transfer the workgroup issued has landed for the calling wave;
 // a workgroup barrier must follow before the LDS is reused.
-template <int D, int HB, bool FILTER, bool STOPPABLE, bool PREFETCHED = false>
+template <int D, int HB, bool FILTER, bool STOPPABLE, bool PREFETCHED = false, int WAVES = kWaves>
 __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)[HB][D / 16],
                                            const float (&wr)[HB][16], const __bf16* __restrict__ Kb,
                                            int key_clamp, int n_keys, SweepOut& o, int* flags,
@@ -217,11 +228,13 @@ __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)
     constexpr int kRowBytes = D * 2;
     constexpr int kPieces = D / 8;         // 16-byte pieces per key row
     constexpr int kRowsPer256 = 256 / kRowBytes;
-    constexpr int kBufBytes = kKeyChunk * kRowBytes;
-    constexpr int kRowsPerLoad = 64 / kPieces;  // key rows covered by one wave-wide 1 KiB load
-    constexpr int kLoads = kKeyChunk / kRowsPerLoad / kWaves;  // loads per wave per chunk
-    static_assert(kKeyChunk % (kRowsPerLoad * kWaves) == 0, "chunk must split evenly over the waves");
-    static_assert(kKeyChunk == 128, "the pipelined loop is written for 4 sub-blocks per chunk");
+    constexpr int kChunk = SweepShape<WAVES>::kChunk;      // keys per LDS buffer
+    constexpr int kBuffers = SweepShape<WAVES>::kBuffers;  // ring length; kBuffers - 1 chunks ahead
+    constexpr int kBufBytes = kChunk * kRowBytes;
+    constexpr int kLoads = kBufBytes / 1024 / WAVES;       // wave-wide 1 KiB loads per wave per chunk
+    static_assert(kBufBytes % (1024 * WAVES) == 0 && kLoads >= 1, "chunk must split evenly over the waves");
+    static_assert(kChunk == 128 || kChunk == 64, "the pipelined loop is written for 4 or 2 sub-blocks per chunk");
+    static_assert(kLoads * (kBuffers - 2) <= 15, "the wait below counts loads in a 4-bit field");
 
     // wave-uniform values live in scalar registers
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -271,13 +284,17 @@ __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)
 #define SI_KREAD(SUBBLOCK, KSTEP) \
     (*reinterpret_cast<const bf16x8*>(lds + kaddr[KSTEP] + (SUBBLOCK) * 32 * kRowBytes))
 
-    // Chunks 0 and 1 in flight; chunk 0 must have landed before its first read.
-    int off_cur = 0, off_next = kBufBytes, off_nn = 2 * kBufBytes;  // LDS buffers: being read, next, filling
+    // The first kBuffers - 1 chunks in flight; chunk 0 must have landed before its first read.
+    // ring[0] is the buffer being read, ring[1] the next one, ..., ring[kBuffers - 1] the one filling.
+    int ring[kBuffers];
+#pragma unroll
+    for (int i = 0; i < kBuffers; ++i) ring[i] = i * kBufBytes;
     if (!PREFETCHED) {
-        SI_FETCH(0, off_cur)
-        SI_FETCH(kKeyChunk, off_next)
+#pragma unroll
+        for (int c = 0; c < kBuffers - 1; ++c) SI_FETCH(c * kChunk, ring[c])
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70 | kLoads);  // vmcnt(kLoads): everything but chunk 1 has landed
+    // vmcnt: everything but the newest kBuffers - 2 chunks has landed
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (kLoads * (kBuffers - 2)));
     __syncthreads();
 
     bf16x8 bq[KS];  // key operand of the sub-block about to be multiplied
@@ -343,48 +360,76 @@ __device__ __forceinline__ int score_sweep(unsigned char* lds, const bf16x8 (&a)
     float r_even = 0.0f;  // epilogue result of the last even sub-block, waiting for its odd partner
     int kc0 = 0;
     bool stop = false;
-    for (; kc0 < n_keys && !stop; kc0 += kKeyChunk) {
-        // Chunk kc0/128 + 2 starts its trip to LDS.  Issued unconditionally (addresses are clamped,
-        // the buffer is unused if the chunk does not exist) so that the vmcnt arithmetic below holds.
-        SI_FETCH(kc0 + 2 * kKeyChunk, off_nn)
-        float sp, s0v, s1v, s2v;
-        SI_STEP(accA, accB, sp, 1)
-        SI_STEP(accB, accA, s0v, 2)
-        SI_STEP(accA, accB, s1v, 3)
-        // The next chunk must be in LDS, and visible to every wave, before its first read below.
-        // A bare barrier: __syncthreads() would add a release fence that waits for every vector
-        // memory operation, i.e. also for the chunk that has just started its trip.  What the
-        // barrier must order is waited for explicitly -- vmcnt(kLoads): only the newest chunk may
-        // be in flight; lgkmcnt(0): this wave's LDS writes (the flags) are done -- and the empty
-        // asm statements keep the compiler from moving memory accesses across it.
-        __builtin_amdgcn_s_waitcnt(0x0070 | kLoads);
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
+    // The next chunk must be in LDS, and visible to every wave, before its first read.
+    // A bare barrier: __syncthreads() would add a release fence that waits for every vector
+    // memory operation, i.e. also for the chunks that have just started their trip.  What the
+    // barrier must order is waited for explicitly -- vmcnt: only the newest kBuffers - 2 chunks may
+    // be in flight; lgkmcnt(0): this wave's LDS writes (the flags) are done -- and the empty
+    // asm statements keep the compiler from moving memory accesses across it.
+#define SI_NEXT_CHUNK_BARRIER()                                               \
+    __builtin_amdgcn_s_waitcnt(0x0070 | (kLoads * (kBuffers - 2)));           \
+    asm volatile("" ::: "memory");                                            \
+    __builtin_amdgcn_s_barrier();                                             \
+    asm volatile("" ::: "memory");
+    for (; kc0 < n_keys && !stop; kc0 += kChunk) {
+        // The chunk kBuffers - 1 ahead starts its trip to LDS.  Issued unconditionally (a chunk past
+        // the key range reads nothing and its buffer is never used) so that the vmcnt arithmetic holds.
+        SI_FETCH(kc0 + (kBuffers - 1) * kChunk, ring[kBuffers - 1])
         int posted = 0;
-        if (STOPPABLE) posted = flags[((kc0 / kKeyChunk) + 1) & 1];  // posted after the previous step
-        {   // from here on the reads go to the next chunk's buffer
-            const int delta = off_next - off_cur;
+        if constexpr (kChunk == 128) {
+            float sp, s0v, s1v, s2v;
+            SI_STEP(accA, accB, sp, 1)
+            SI_STEP(accB, accA, s0v, 2)
+            SI_STEP(accA, accB, s1v, 3)
+            SI_NEXT_CHUNK_BARRIER()
+            if (STOPPABLE) posted = flags[((kc0 / kChunk) + 1) & 1];  // posted after the previous step
+            {   // from here on the reads go to the next chunk's buffer
+                const int delta = ring[1] - ring[0];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) kaddr[ks] += delta;
-        }
-        SI_STEP(accB, accA, s2v, 0)
-        // even sub-blocks stay in the low half-wave, odd ones in the high half
-        const float res_prev = half ? sp : r_even;   // keys kc0 - 64 + lane (previous chunk)
-        const float res_cur = half ? s1v : s0v;      // keys kc0 + lane
-        r_even = s2v;
-        if (!FILTER || __builtin_amdgcn_ballot_w64((res_prev > theta) | (res_cur > theta)) != 0ull) {
-            SI_EMIT(res_prev, kc0 - 64)
-            SI_EMIT(res_cur, kc0)
+                for (int ks = 0; ks < KS; ++ks) kaddr[ks] += delta;
+            }
+            SI_STEP(accB, accA, s2v, 0)
+            // even sub-blocks stay in the low half-wave, odd ones in the high half
+            const float res_prev = half ? sp : r_even;   // keys kc0 - 64 + lane (previous chunk)
+            const float res_cur = half ? s1v : s0v;      // keys kc0 + lane
+            r_even = s2v;
+            if (!FILTER || __builtin_amdgcn_ballot_w64((res_prev > theta) | (res_cur > theta)) != 0ull) {
+                SI_EMIT(res_prev, kc0 - 64)
+                SI_EMIT(res_cur, kc0)
+            }
+        } else {
+            // two sub-blocks per chunk: the scores of chunk c - 1 are complete after the first step
+            // of chunk c (its odd sub-block's epilogue runs under the MFMAs of this chunk's even one)
+            float e_odd, e_even;
+            SI_STEP(accA, accB, e_odd, 1)
+            SI_NEXT_CHUNK_BARRIER()
+            if (STOPPABLE) posted = flags[((kc0 / kChunk) + 1) & 1];
+            {
+                const int delta = ring[1] - ring[0];
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) kaddr[ks] += delta;
+            }
+            SI_STEP(accB, accA, e_even, 0)
+            const float res_prev = half ? e_odd : r_even;  // keys kc0 - 64 + lane (previous chunk)
+            r_even = e_even;
+            if (!FILTER || __builtin_amdgcn_ballot_w64(res_prev > theta) != 0ull) {
+                SI_EMIT(res_prev, kc0 - 64)
+            }
         }
         if (STOPPABLE) {
             if (n_cand >= trigger) {  // wave-uniform, rare
-                if (lane == 0) flags[(kc0 / kKeyChunk) & 1] = 1;
+                if (lane == 0) flags[(kc0 / kChunk) & 1] = 1;
             }
             stop = __builtin_amdgcn_readfirstlane(posted) != 0;
         }
-        const int t_ = off_cur; off_cur = off_next; off_next = off_nn; off_nn = t_;
+        {   // the ring moves on by one buffer
+            const int t_ = ring[0];
+#pragma unroll
+            for (int i = 0; i + 1 < kBuffers; ++i) ring[i] = ring[i + 1];
+            ring[kBuffers - 1] = t_;
+        }
     }
+#undef SI_NEXT_CHUNK_BARRIER
     {   // drain: the last sub-block's epilogue and the last 64 scores
         float s_ = 0.0f;
 #pragma unroll

@@ -98,10 +98,23 @@ enum PhaseWord {
     kPhaseChunks = 8,     // count: 128-key steps swept
     kPhaseMerges = 9,     // count: merges
     kPhaseLaunches = 10,  // count: launches this workgroup took part in
-    kPhaseWords = 16
+    // ticks, parts of kPhaseMerge: barrier behind the stopped sweep + next key chunks requested,
+    // row read into registers, radix descent, kept keys written back + barrier
+    kPhaseMergeSync = 11, kPhaseMergeLoad = 12, kPhaseMergeRadix = 13, kPhaseMergeKeep = 14,
+    // ticks, parts of kPhaseFinal: row read, exact radix cut, kept keys to LDS (+ pads), sort, write-out
+    kPhaseFinalLoad = 15, kPhaseFinalRadix = 16, kPhaseFinalKeep = 17, kPhaseFinalSort = 18,
+    kPhaseFinalWrite = 19,
+    // set, not added: where the workgroup ran (hardware id register of its wave 0: compute unit,
+    // shader array and engine; and the XCC id register), to see which workgroups shared a unit
+    kPhaseHwId = 20, kPhaseXccId = 21,
+    // ticks: first instruction of the workgroup, relative to the earliest tick the host finds
+    kPhaseStartTick = 22,
+    kPhaseWords = 32
 };
+// Phase-change log of two workgroups, behind the per-workgroup words (see fused.hip).
+constexpr int kPhaseTraceEvents = 2048;
 
-enum ProfileClass { kProfScore = 0, kProfFilterScores = 1, kProfCompact = 2, kProfFinalize = 3, kProfInit = 4, kProfFused = 5 };
+enum ProfileClass { kProfScore = 0, kProfFilterScores = 1, kProfCompact = 2, kProfFinalize = 3, kProfInit = 4, kProfFused = 5, kProfFusedNarrow = 6 };
 
 // Kernel launchers (each enqueues exactly one kernel on `stream`).
 // Dense fp32 tile [B, tile_rows, tile_cols] of queries [s0, s0+rows) x keys [t0, t0+width).
@@ -128,13 +141,17 @@ hipError_t launch_finalize(const RowBuffers& rb, int32_t B, int32_t rows, int32_
                            float* out_score, hipStream_t stream);
 
 // Single-pass schedule: queries [s_begin, s_begin + rows) of every batch in one launch.
-// slots: n_slots * 8 row buffers of slots.cap >= 2k + 384 keys; *counter must be zero.
+// waves: 8 (wide workgroups, one per compute unit) or 4 (narrow, two per compute unit); at most
+// n_workgroups are launched.  slots: n_workgroups * waves <= 2048 row buffers of slots.cap >=
+// 2k + 384 keys; *counter must be zero.
 // phase: nullptr, or n_slots * kPhaseWords words the instrumented kernel variant adds its phase
-// times to (D = 128, 33..64 heads, k <= 1024 only).
+// times to: phase_slots >= n_workgroups blocks of kPhaseWords, then two logs of kPhaseTraceEvents
+// words (D = 128, 33..64 heads, k <= 1024 only).
 hipError_t launch_fused(const void* q, const void* K, const float* w, const si_dims& d, int32_t m,
                         int32_t mask_mode, int32_t k, int32_t s_begin, int32_t rows,
-                        const RowBuffers& slots, int32_t n_slots, int32_t* counter, int32_t* out_idx,
-                        float* out_score, unsigned long long* phase, hipStream_t stream);
+                        const RowBuffers& slots, int32_t waves, int32_t n_workgroups, int32_t* counter,
+                        int32_t* out_idx, float* out_score, unsigned long long* phase, int32_t phase_slots,
+                        hipStream_t stream);
 hipError_t launch_zero_ints(int32_t* p, int32_t n, hipStream_t stream);
 
 }  // namespace si

@@ -65,34 +65,61 @@ struct StreamKeys {
 };
 
 // Threshold key `thr` and count `kept` such that exactly `kept` of the row's n distinct keys
-// are >= thr, with k <= kept <= max(k, limit).  MSB-first radix descent, 8 bits per pass; it
+// are >= thr, with k <= kept <= max(k, limit).  MSB-first radix descent, up to 8 bits per pass; it
 // stops as soon as the bin holding the k-th largest key is small enough for `kept` to respect
 // the limit (limit == k: exact selection).  Requires n > k.  Wave-uniform arguments.
+//
+// The descent starts at the highest bit in which two score words of the row differ (one OR / AND
+// scan of the keys): the candidates of a row are the upper tail of its score distribution, so their
+// sign and exponent bits agree, and a first pass over those bits would put every key into one or
+// two bins -- no information, and 64 lanes adding to the same LDS word serialise.  Windows never
+// straddle the boundary between the score word and the index word, so each pass works on one
+// 32-bit half of the keys.
 template <typename Keys>
 __device__ inline key64_t wave_radix_kth(const Keys& keys, int k, int limit, int* hist, int* kept) {
     const int lane = threadIdx.x & 63;
-    key64_t prefix = 0ull;
+    uint32_t any_hi = 0u, all_hi = 0xFFFFFFFFu;
+    keys.sweep([&](key64_t key, bool valid) {
+        const uint32_t hi = static_cast<uint32_t>(key >> 32);
+        any_hi |= valid ? hi : 0u;
+        all_hi &= valid ? hi : 0xFFFFFFFFu;
+    });
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        any_hi |= __shfl_xor(any_hi, off);
+        all_hi &= __shfl_xor(all_hi, off);
+    }
+    const uint32_t diff_hi = __builtin_amdgcn_readfirstlane(any_hi ^ all_hi);
+    // highest undecided bit of the 64-bit key; equal scores everywhere: the index word decides
+    int top = diff_hi != 0u ? 63 - __builtin_clz(diff_hi) : 31;
+    key64_t prefix = top >= 32
+        ? static_cast<key64_t>(__builtin_amdgcn_readfirstlane(all_hi) & ~((2u << (top - 32)) - 1u)) << 32
+        : static_cast<key64_t>(__builtin_amdgcn_readfirstlane(all_hi)) << 32;
     int need = k;
     int bin = 0;
-    for (int shift = 56; shift >= 0; shift -= 8) {
+    for (;;) {
+        const int shift = max(top - 7, top >= 32 ? 32 : 0);  // this pass decides bits [shift, top]
+        const int nbits = top - shift + 1;
+        const uint32_t dmask = (1u << nbits) - 1u;
 #pragma unroll
         for (int i = 0; i < 4; ++i) hist[lane + 64 * i] = 0;
         __builtin_amdgcn_wave_barrier();
         if (shift >= 32) {
             // digits of the score word: 32-bit arithmetic on the high half of the key
             const int sh = shift - 32;
-            const uint32_t want = sh == 24 ? 0u : static_cast<uint32_t>(prefix >> 32) >> (sh + 8);
+            const bool whole = top == 63;  // nothing above the window
+            const uint32_t want = whole ? 0u : static_cast<uint32_t>(prefix >> 32) >> (top - 31);
             keys.sweep([&](key64_t key, bool valid) {
                 const uint32_t hi = static_cast<uint32_t>(key >> 32);
-                const bool in_prefix = (sh == 24) || ((hi >> (sh + 8)) == want);
-                if (valid && in_prefix) atomicAdd(&hist[(hi >> sh) & 255u], 1);
+                const bool in_prefix = whole || ((hi >> (top - 31)) == want);
+                if (valid && in_prefix) atomicAdd(&hist[(hi >> sh) & dmask], 1);
             });
         } else {
             // equal scores: digits of the index word
-            const key64_t want = prefix >> (shift + 8);
+            const key64_t want = prefix >> (top + 1);
             keys.sweep([&](key64_t key, bool valid) {
-                const bool in_prefix = (key >> (shift + 8)) == want;
-                if (valid && in_prefix) atomicAdd(&hist[(key >> shift) & 255ull], 1);
+                const bool in_prefix = (key >> (top + 1)) == want;
+                if (valid && in_prefix) atomicAdd(&hist[static_cast<uint32_t>(key >> shift) & dmask], 1);
             });
         }
         __builtin_amdgcn_wave_barrier();
@@ -126,7 +153,8 @@ __device__ inline key64_t wave_radix_kth(const Keys& keys, int k, int limit, int
         bin = __shfl(new_bin, src);
         prefix |= static_cast<key64_t>(digit) << shift;
         // keys >= prefix: the (k - need) in higher bins plus this whole bin
-        if (k - need + bin <= limit) break;
+        if (k - need + bin <= limit || shift == 0) break;
+        top = shift - 1;
     }
     *kept = k - need + bin;
     return prefix;

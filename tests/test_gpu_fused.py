@@ -24,13 +24,15 @@ def _rand_problem(seed, B, S, H, D, T):
 
 
 def _run(fn_name, q, K, w, m, k, mask, *tiling):
+    """fn_name: "fused" (wide workgroups), "narrow" (the 4-query shape) or "tiled"."""
     B, S, H, D = q.shape
     T = K.shape[1]
     out_idx = torch.full((B, S, k), -7, dtype=torch.int32, device=DEV)
     out_score = torch.full((B, S, k), 123.0, dtype=torch.float32, device=DEV)
-    if fn_name == "fused":
+    if fn_name in ("fused", "narrow"):
         ws = torch.empty(P.si_fused_workspace_bytes(B, S, H, D, T, k, tiling[0]), dtype=torch.uint8, device=DEV)
-        P.si_indexer_topk_fused(q, K, w, m, k, mask, tiling[0], out_idx, out_score, ws)
+        P.si_indexer_topk_fused_shape(q, K, w, m, k, mask, tiling[0], 8 if fn_name == "fused" else 4,
+                                      out_idx, out_score, ws)
     else:
         ws = torch.empty(P.si_workspace_bytes(B, S, H, D, T, k, *tiling), dtype=torch.uint8, device=DEV)
         P.si_indexer_topk_tiled(q, K, w, m, k, mask, tiling[0], tiling[1], out_idx, out_score, ws)
@@ -66,6 +68,7 @@ def test_fused_matches_oracle_and_tiled(oracle, B, S, H, D, T, m, k, mask, c_S):
     assert stats["min_recall"] >= 1.0 - 2.0 / k, stats
     tiled = _run("tiled", qd, Kd, wd, m, k, mask, min(S, 128), min(T, 384))
     assert _same(fused, tiled)
+    assert _same(fused, _run("narrow", qd, Kd, wd, m, k, mask, c_S))
 
 
 def test_fused_adversarial_ascending_scores(oracle):
@@ -83,6 +86,7 @@ def test_fused_adversarial_ascending_scores(oracle):
     fused = _run("fused", qd, Kd, wd, m, k, 0, 0)
     tiled = _run("tiled", qd, Kd, wd, m, k, 0, S, 4096)
     assert _same(fused, tiled)
+    assert _same(fused, _run("narrow", qd, Kd, wd, m, k, 0, 0))
     stats = parity.check_rows(
         oracle, W.bf16_bits(q).reshape(S, H, D), w.numpy().reshape(S, H), W.bf16_bits(K),
         np.zeros(S, dtype=np.int32), np.arange(S, dtype=np.int64), m, k, 0,
@@ -117,6 +121,8 @@ def test_fused_rows_filled_to_the_brim(oracle, k):
     assert stats["mean_recall"] > 0.999, stats
     tiled = _run("tiled", qd, Kd, wd, m, k, 0, S, 777)
     assert _same(fused, tiled)
+    # narrow shape: 64-key steps, so the count climbs in other increments; same bits, no marker
+    assert _same(fused, _run("narrow", qd, Kd, wd, m, k, 0, 0))
 
 
 def test_default_entry_point_falls_back_to_the_tiled_plan():
@@ -137,7 +143,7 @@ def test_default_entry_point_falls_back_to_the_tiled_plan():
     torch.cuda.synchronize()
     prof = P.si_profile_read()
     P.si_profile_enable(False)
-    assert prof["fused"][1] == 0 and prof["score_tile"][1] > 0
+    assert prof["fused"][1] == 0 and prof["fused_narrow"][1] == 0 and prof["score_tile"][1] > 0
     assert _same((out_idx, out_score), fused)
     # k = 4096: beyond the single-pass schedule
     k2 = 4096
@@ -150,7 +156,7 @@ def test_default_entry_point_falls_back_to_the_tiled_plan():
     torch.cuda.synchronize()
     prof = P.si_profile_read()
     P.si_profile_enable(False)
-    assert prof["fused"][1] == 0 and prof["score_tile"][1] > 0
+    assert prof["fused"][1] == 0 and prof["fused_narrow"][1] == 0 and prof["score_tile"][1] > 0
     assert torch.equal(oi[:, :, :k], fused[0][:, :, :k].where(fused[0][:, :, :k] >= 0, oi[:, :, :k]))
     valid = (oi[0] >= 0).sum(dim=1).cpu().numpy()
     t = np.arange(S)
@@ -192,6 +198,7 @@ def test_fused_and_tiled_agree_on_random_shapes_and_score_patterns(oracle, c):
     fused = _run("fused", qd, Kd, wd, c["m"], c["k"], c["mask"], c["c_S"])
     tiled = _run("tiled", qd, Kd, wd, c["m"], c["k"], c["mask"], min(S, c["cs2"]), min(T, c["c_T"]))
     assert _same(fused, tiled)
+    assert _same(fused, _run("narrow", qd, Kd, wd, c["m"], c["k"], c["mask"], c["c_S"]))
     # structure: valid slots first, as many as there are legal keys (up to k), then pads
     valid = (fused[0] >= 0).sum(dim=2).cpu().numpy()
     t = np.arange(S)
@@ -209,3 +216,25 @@ def test_fused_and_tiled_agree_on_random_shapes_and_score_patterns(oracle, c):
             n_threads=parity.host_threads())
         assert np.array_equal(fused[0][0].cpu().numpy()[rows], ora_idx)
         assert np.array_equal(fused[1][0].cpu().numpy()[rows], ora_score.astype(np.float32))
+
+
+def test_narrow_shape_with_staggered_start_many_items(oracle):
+    """Enough work items (>= 4 per workgroup of a full grid) that the narrow shape's second half of
+    the grid starts on the shortest items: every row still comes out once, bit-identical to the
+    wide shape, and sampled rows agree with the oracle."""
+    B, S, H, D, m, k = 1, 16384, 8, 32, 2, 24
+    T = S // m
+    q, K, w = _rand_problem(99, B, S, H, D, T)
+    qd, Kd, wd = q.to(DEV), K.to(DEV), w.to(DEV)
+    print(f"narrow stagger S={S} T={T} k={k}", flush=True)
+    wide = _run("fused", qd, Kd, wd, m, k, 1, 0)
+    narrow = _run("narrow", qd, Kd, wd, m, k, 1, 0)
+    assert _same(wide, narrow)
+    narrow2 = _run("narrow", qd, Kd, wd, m, k, 1, 5000)  # launches of 5000 queries: ragged last one
+    assert _same(wide, narrow2)
+    rows = np.unique(np.concatenate([np.arange(0, 64), np.arange(S - 64, S), np.arange(0, S, 97)]))
+    stats = parity.check_rows(
+        oracle, W.bf16_bits(q)[0, rows], w.numpy()[0, rows], W.bf16_bits(K),
+        np.zeros(len(rows), dtype=np.int32), rows, m, k, 1,
+        narrow[0].cpu().numpy()[0, rows], narrow[1].cpu().numpy()[0, rows])
+    assert stats["min_recall"] >= 1.0 - 2.0 / k, stats

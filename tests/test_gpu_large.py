@@ -69,6 +69,16 @@ def _run_default(wl, q, K, w, nbytes):
     return out_idx, out_score
 
 
+def _run_shape(wl, q, K, w, shape):
+    """The single-pass schedule with an explicit workgroup shape (8 = wide, 4 = narrow)."""
+    out_idx = torch.empty((wl.B, wl.S, wl.k), dtype=torch.int32, device=DEV)
+    out_score = torch.empty((wl.B, wl.S, wl.k), dtype=torch.float32, device=DEV)
+    ws = torch.empty(P.si_fused_workspace_bytes(wl.B, wl.S, wl.H, wl.D, wl.T, wl.k), dtype=torch.uint8, device=DEV)
+    P.si_indexer_topk_fused_shape(q, K, w, wl.m, wl.k, wl.mask_mode, 0, shape, out_idx, out_score, ws)
+    torch.cuda.synchronize()
+    return out_idx, out_score
+
+
 def _same_bits(a, b):
     return torch.equal(a[0], b[0]) and torch.equal(a[1].view(torch.int32), b[1].view(torch.int32))
 
@@ -91,7 +101,21 @@ def test_flash_64k_sampled_rows(oracle):
     # the single-pass schedule in its own small workspace: same bits
     fused_bytes = P.si_fused_workspace_bytes(wl.B, wl.S, wl.H, wl.D, wl.T, wl.k)
     assert 0 < fused_bytes < 64 * 2**20
-    assert _same_bits(out, _run_default(wl, q, K, w, fused_bytes))
+    # ... and the profile classes record which schedule the default entry point took
+    P.si_profile_reset()
+    P.si_profile_enable(True)
+    default = _run_default(wl, q, K, w, fused_bytes)
+    prof = P.si_profile_read()
+    P.si_profile_enable(False)
+    assert _same_bits(out, default)
+    shape = P.si_fused_shape_for(wl.B, wl.S, wl.H, wl.D, wl.T, wl.m, wl.k, wl.mask_mode)
+    ran = {name: n for name, (_, n) in prof.items() if n}
+    _say(f"flash_64k default entry point: predicted shape {shape}, launches {ran}")
+    assert prof["score_tile"][1] == 0
+    assert (prof["fused_narrow"][1] > 0) == (shape == 4) and (prof["fused"][1] > 0) == (shape == 8)
+    # both workgroup shapes, chosen explicitly: same bits
+    assert _same_bits(out, _run_shape(wl, q, K, w, 8))
+    assert _same_bits(out, _run_shape(wl, q, K, w, 4))
 
 
 def test_flash_256k_key_tile_sweep_is_bit_identical(oracle):
@@ -108,7 +132,9 @@ def test_flash_256k_key_tile_sweep_is_bit_identical(oracle):
             assert stats["mean_recall"] > 0.9999 and stats["min_recall"] >= 1.0 - 2.0 / wl.k
         else:
             assert _same_bits(out, ref), c_T
-    _say("flash_256k single pass")
+    _say("flash_256k single pass, both workgroup shapes")
+    assert _same_bits(ref, _run_shape(wl, q, K, w, 8))
+    assert _same_bits(ref, _run_shape(wl, q, K, w, 4))
     assert _same_bits(ref, _run_default(wl, q, K, w, P.si_fused_workspace_bytes(wl.B, wl.S, wl.H, wl.D, wl.T, wl.k)))
 
 
