@@ -133,7 +133,7 @@ def main() -> int:
                     help="single-pass schedule: queries per workgroup (8 wide, 4 narrow, 0 = the library's choice)")
     ap.add_argument("--c-s", type=int, default=0, help="explicit query tile (0 = planned)")
     ap.add_argument("--c-t", type=int, default=0, help="explicit key tile (0 = planned)")
-    ap.add_argument("--oracle-rows", type=int, default=256,
+    ap.add_argument("--oracle-rows", type=int, default=1536,
                     help="rows of the workload the CPU oracle is timed (and checked) on; 0 = skip")
     ap.add_argument("--seq-len", type=int, default=0, help="override S of the workload (T = S/m follows)")
     ap.add_argument("--topk", type=int, default=0, help="override k of the workload")

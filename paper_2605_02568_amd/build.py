@@ -30,13 +30,17 @@ def _hipcc() -> str:
     return "hipcc"
 
 
+# the sources of the indexer top-k path (kernels, driver, public header), in hashing order
+INDEXER_SOURCES = ("driver.hip", "fused.hip", "score_sweep.h", "score_tile.hip", "si_internal.h",
+                   "topk.hip", "topk_wave.h")
+
+
 def source_hash() -> str:
-    """First 16 hex digits of the SHA-256 over the library's sources (kernels, driver, public
-    header), in a fixed order: identifies the build a measurement was taken on."""
+    """First 16 hex digits of the SHA-256 over the sources of the indexer top-k path: identifies
+    the build a measurement under profiles/ was taken on."""
     import hashlib
     h = hashlib.sha256()
-    files = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".h")))
-    files.append(os.path.join(INCLUDE, "streamindex.h"))
+    files = [os.path.join(CSRC, f) for f in INDEXER_SOURCES] + [os.path.join(INCLUDE, "streamindex.h")]
     for f in files:
         h.update(os.path.basename(f).encode())
         h.update(open(f, "rb").read())
