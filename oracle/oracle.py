@@ -71,6 +71,11 @@ def lib():
             POINTER(c_uint16), POINTER(c_float), POINTER(c_uint16), POINTER(c_int32),
             POINTER(c_int64), c_int64, c_int32, c_int32, c_int64, c_int32, c_int32, c_int32,
             POINTER(c_int32), POINTER(c_double), c_int32]
+        L.si_oracle_sparse_attention_rows.restype = c_int32
+        L.si_oracle_sparse_attention_rows.argtypes = [
+            POINTER(c_uint16), POINTER(c_uint16), POINTER(c_int32), POINTER(c_int32), POINTER(c_int64),
+            c_int64, c_int32, c_int32, c_int64, c_int32, c_int32, c_int32, c_int32, c_double,
+            POINTER(c_double), c_int32]
         L.si_oracle_stream_topk.restype = c_int32
         L.si_oracle_stream_topk.argtypes = [
             POINTER(c_double), c_int64, POINTER(c_int64), c_int32, POINTER(c_int32),
@@ -167,6 +172,30 @@ def topk_all(q, K, w, m: int, k: int, mask_mode: int, n_threads: int = 1):
     idx, sc = topk_rows(q.reshape(B * S, H, D), _f32(w).reshape(B * S, H), K, b, t, m, k,
                         mask_mode, n_threads)
     return idx.reshape(B, S, k), sc.reshape(B, S, k)
+
+
+def sparse_attention_rows(qa_rows, K, idx_rows, b_of_row, t_of_row, m: int, mask_mode: int,
+                          n_win: int, scale: float, n_threads: int = 1):
+    """Attention of the listed query rows over TopK(t) U Window(t) (see si_oracle.h).
+    qa_rows [n,H,D] uint16, K [B,T,D] uint16, idx_rows [n,k] int32 -> [n,H,D] float64."""
+    qa_rows, K = _u16(qa_rows), _u16(K)
+    idx_rows = np.ascontiguousarray(idx_rows, dtype=np.int32)
+    b_of_row = np.ascontiguousarray(b_of_row, dtype=np.int32)
+    t_of_row = np.ascontiguousarray(t_of_row, dtype=np.int64)
+    n, H, D = qa_rows.shape
+    B, T, D2 = K.shape
+    k = idx_rows.shape[1]
+    assert D2 == D and idx_rows.shape == (n, k) and b_of_row.shape == (n,) and t_of_row.shape == (n,)
+    assert n == 0 or (0 <= b_of_row.min() and b_of_row.max() < B and t_of_row.min() >= 0)
+    out = np.empty((n, H, D), dtype=np.float64)
+    rc = lib().si_oracle_sparse_attention_rows(
+        _p(qa_rows, c_uint16), _p(K, c_uint16), _p(idx_rows, c_int32), _p(b_of_row, c_int32),
+        _p(t_of_row, c_int64), n, H, D, T, m, k, mask_mode, n_win, float(scale), _p(out, c_double),
+        n_threads)
+    if rc == -2:
+        raise ValueError("index outside [-1, T)")
+    assert rc == 0, rc
+    return out
 
 
 def stream_topk(scores, perm, k: int):

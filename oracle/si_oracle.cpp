@@ -9,6 +9,7 @@
 #include <cstring>
 #include <limits>
 #include <queue>
+#include <set>
 #include <thread>
 #include <utility>
 #include <vector>
@@ -220,6 +221,66 @@ int32_t si_oracle_chunked_topk_row(const double* scores, int64_t T, int64_t lega
         const bool valid = e.idx < legal;
         out_idx[j] = valid ? static_cast<int32_t>(e.idx) : -1;
         out_score[j] = valid ? e.score : ninf;
+    }
+    return 0;
+}
+
+int32_t si_oracle_sparse_attention_rows(const uint16_t* qa_rows, const uint16_t* K,
+                                        const int32_t* idx_rows, const int32_t* b_of_row,
+                                        const int64_t* t_of_row, int64_t n_rows, int32_t H,
+                                        int32_t D, int64_t T, int32_t m, int32_t k,
+                                        int32_t mask_mode, int32_t n_win, double scale,
+                                        double* out, int32_t n_threads) {
+    if (!qa_rows || !K || !idx_rows || !b_of_row || !t_of_row || !out) return -1;
+    if (n_rows < 0 || H <= 0 || D <= 0 || T <= 0 || m < 1 || k < 1 || n_win < 0) return -1;
+    if (mask_mode != 0 && mask_mode != 1) return -1;
+    for (int64_t i = 0; i < n_rows * k; ++i)
+        if (idx_rows[i] < -1 || idx_rows[i] >= T) return -2;
+
+    auto one_row = [&](int64_t r) {
+        const int64_t L = si_oracle_legal_count(t_of_row[r], T, m, mask_mode);
+        // U(t): the list's valid entries and the window, as a set, ascending
+        std::set<int64_t> U;
+        for (int32_t j = 0; j < k; ++j)
+            if (idx_rows[r * k + j] >= 0) U.insert(idx_rows[r * k + j]);
+        for (int64_t s = std::max<int64_t>(0, L - n_win); s < L; ++s) U.insert(s);
+        const uint16_t* Kb = K + static_cast<int64_t>(b_of_row[r]) * T * D;
+        double* o = out + r * H * D;
+        for (int64_t i = 0; i < static_cast<int64_t>(H) * D; ++i) o[i] = 0.0;
+        if (U.empty()) return;
+        std::vector<double> logit(U.size()), p(U.size());
+        for (int32_t h = 0; h < H; ++h) {
+            const uint16_t* qh = qa_rows + (r * H + h) * D;
+            size_t n = 0;
+            double top = -std::numeric_limits<double>::infinity();
+            for (int64_t s : U) {
+                double dot = 0.0;
+                for (int32_t d = 0; d < D; ++d) dot += bf16_to_double(qh[d]) * bf16_to_double(Kb[s * D + d]);
+                logit[n] = scale * dot;
+                top = std::max(top, logit[n]);
+                ++n;
+            }
+            double denom = 0.0;
+            for (size_t i = 0; i < n; ++i) {
+                p[i] = std::exp(logit[i] - top);
+                denom += p[i];
+            }
+            n = 0;
+            for (int64_t s : U) {
+                const double ps = p[n++] / denom;
+                for (int32_t d = 0; d < D; ++d) o[h * D + d] += ps * bf16_to_double(Kb[s * D + d]);
+            }
+        }
+    };
+    if (n_threads <= 1) {
+        for (int64_t r = 0; r < n_rows; ++r) one_row(r);
+    } else {
+        std::vector<std::thread> pool;
+        for (int32_t i = 0; i < n_threads; ++i)
+            pool.emplace_back([&, i] {
+                for (int64_t r = i; r < n_rows; r += n_threads) one_row(r);
+            });
+        for (auto& th : pool) th.join();
     }
     return 0;
 }

@@ -23,7 +23,10 @@
  * ReLU(x) - ReLU(-x) = x identity against a plain mat-vec, exact power-of-two
  * scaling, single-head non-negative case against a library sort, key
  * permutation invariance, Algorithm 1 and Algorithm 2 agreeing with the full
- * sort, footprint figures printed in the paper.
+ * sort, footprint figures printed in the paper.  The attention consumer
+ * (si_oracle_sparse_attention_rows): dense masked softmax attention in numpy,
+ * constant-value rows, zero queries (uniform weights), window-only = local
+ * attention, list order and duplicates, a huge scale (argmax), empty sets.
  * Absolute score values on random inputs have no figure in the paper to compare
  * with; they are pinned through the identities and the brute-force case only.
  */
@@ -78,6 +81,24 @@ int32_t si_oracle_stream_topk(const double* scores, int64_t L, const int64_t* pe
 int32_t si_oracle_chunked_topk_row(const double* scores, int64_t T, int64_t legal,
                                    int32_t k, int64_t c_T, int32_t variant,
                                    int32_t* out_idx, double* out_score);
+
+/* The consumer of the index lists (Section 3, step 4: "a sparse attention kernel reads only
+ * TopK(t) U Window(t) for each query"), as this build reads it (the paper gives no formula):
+ *   K_C is the compressed key/value cache: a key's row is also its value row (Section 3, step 1);
+ *   TopK(t)   = the entries >= 0 of the query's index list (any order, -1 = pad);
+ *   Window(t) = the last min(n_win, legal(t)) legal keys: legal(t)-n_win .. legal(t)-1;
+ *   U(t)      = TopK(t) U Window(t) as a SET (a key in both counts once);
+ *   out[t,h,:] = sum_{s in U} p_s K_C[s,:],  p = softmax over U of scale * <qa[t,h,:], K_C[s,:]>,
+ *   and out = 0 when U is empty.
+ * qa_rows: [n_rows, H, D] bf16 bits, K: [B, T, D] bf16 bits, idx_rows: [n_rows, k] (entries -1 or
+ * in [0, T)), out: [n_rows, H, D] fp64.  Every product, exponential and sum in double; the set is
+ * visited in ascending key order.  Returns 0, -1 on bad arguments, -2 on an index outside [-1, T). */
+int32_t si_oracle_sparse_attention_rows(const uint16_t* qa_rows, const uint16_t* K,
+                                        const int32_t* idx_rows, const int32_t* b_of_row,
+                                        const int64_t* t_of_row, int64_t n_rows, int32_t H,
+                                        int32_t D, int64_t T, int32_t m, int32_t k,
+                                        int32_t mask_mode, int32_t n_win, double scale,
+                                        double* out, int32_t n_threads);
 
 /* Bytes of the [B, S, H, T] fp32 intermediate that the method avoids. */
 uint64_t si_oracle_materialize_bytes(int64_t B, int64_t S, int64_t H, int64_t T);
