@@ -9,5 +9,5 @@ from .binding import (  # noqa: F401
     SI_OK, StreamIndexError, load, si_fused_workspace_bytes, si_indexer_topk, si_fused_shape_for, si_indexer_topk_fused, si_indexer_topk_fused_shape, si_indexer_topk_static,
     si_indexer_topk_tiled, si_last_hip_error,
     si_materialize_bytes, si_plan_tiles, si_profile_enable, si_profile_phases, si_profile_read, si_profile_reset,
-    si_score_tile, si_strerror, si_topk_from_scores, si_version, si_wall_clock_khz, si_workspace_bytes,
+    si_score_tile, si_sparse_attention, si_strerror, si_topk_from_scores, si_version, si_wall_clock_khz, si_workspace_bytes,
 )

@@ -5,7 +5,8 @@ from __future__ import annotations
 
 import ctypes
 import os
-from ctypes import POINTER, Structure, byref, c_char_p, c_double, c_int32, c_int64, c_size_t, c_uint64, c_void_p
+from ctypes import (POINTER, Structure, byref, c_char_p, c_double, c_float, c_int32, c_int64, c_size_t,
+                    c_uint64, c_void_p)
 
 import torch  # first: makes the process use torch's HIP runtime, which the library then shares
 
@@ -25,7 +26,7 @@ PROFILE_CLASS_NAMES = ("score_tile", "filter_scores", "compact", "finalize", "in
 EXPORTS = (
     "si_plan_tiles", "si_workspace_bytes", "si_indexer_topk", "si_indexer_topk_tiled",
     "si_fused_workspace_bytes", "si_indexer_topk_fused", "si_indexer_topk_fused_shape",
-    "si_fused_shape_for", "si_indexer_topk_static",
+    "si_fused_shape_for", "si_indexer_topk_static", "si_sparse_attention",
     "si_score_tile", "si_topk_from_scores", "si_materialize_bytes", "si_profile_enable",
     "si_profile_reset", "si_profile_read", "si_profile_phases", "si_wall_clock_khz", "si_strerror",
     "si_last_hip_error",
@@ -86,6 +87,9 @@ def load():
     L.si_indexer_topk_static.restype = c_int32
     L.si_indexer_topk_static.argtypes = [c_void_p, c_void_p, c_void_p, POINTER(si_dims), c_int32,
                                          c_int32, c_int32, c_void_p, c_void_p, c_void_p]
+    L.si_sparse_attention.restype = c_int32
+    L.si_sparse_attention.argtypes = [c_void_p, c_void_p, c_void_p, POINTER(si_dims), c_int32, c_int32,
+                                      c_int32, c_int32, c_float, c_void_p, c_void_p]
     L.si_score_tile.restype = c_int32
     L.si_score_tile.argtypes = [c_void_p, c_void_p, c_void_p, POINTER(si_dims), c_int32, c_int32,
                                 c_int32, c_int32, c_int32, c_int32, c_void_p, c_void_p]
@@ -237,6 +241,23 @@ def si_indexer_topk_static(q, K, w, m, k, mask_mode, out_idx, out_score, stream=
         _dev_ptr(w, torch.float32, "w"), byref(dims), m, k, mask_mode,
         _dev_ptr(out_idx, torch.int32, "out_idx"), _dev_ptr(out_score, torch.float32, "out_score"),
         _stream_handle(stream)), "si_indexer_topk_static")
+
+
+def si_sparse_attention(qa, Kc, idx, m, mask_mode, n_win, scale, out, stream=None):
+    """Attention over TopK(t) U Window(t): qa [B,S,H_A,D] bf16, Kc [B,T,D] bf16, idx [B,S,k] int32,
+    out [B,S,H_A,D] f32."""
+    if qa.dim() != 4 or Kc.dim() != 3 or idx.dim() != 3:
+        raise ValueError("qa must be [B,S,H_A,D], Kc [B,T,D], idx [B,S,k]")
+    B, S, H, D = qa.shape
+    if Kc.shape[0] != B or Kc.shape[2] != D or tuple(idx.shape[:2]) != (B, S):
+        raise ValueError(f"shape mismatch: qa {tuple(qa.shape)}, Kc {tuple(Kc.shape)}, idx {tuple(idx.shape)}")
+    if tuple(out.shape) != (B, S, H, D):
+        raise ValueError(f"out must be {(B, S, H, D)}")
+    dims = si_dims(B, S, H, D, Kc.shape[1])
+    _check(load().si_sparse_attention(
+        _dev_ptr(qa, torch.bfloat16, "qa"), _dev_ptr(Kc, torch.bfloat16, "Kc"),
+        _dev_ptr(idx, torch.int32, "idx"), byref(dims), m, idx.shape[2], mask_mode, n_win, float(scale),
+        _dev_ptr(out, torch.float32, "out"), _stream_handle(stream)), "si_sparse_attention")
 
 
 def si_score_tile(q, K, w, m, mask_mode, s0, t0, c_S, c_T, tile, stream=None):

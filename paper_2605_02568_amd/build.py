@@ -12,7 +12,7 @@ INCLUDE = os.path.join(ROOT, "include")
 OBJ_DIR = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libstreamindex.so")
 
-SOURCES = ["score_tile.hip", "fused.hip", "topk.hip", "driver.hip"]
+SOURCES = ["score_tile.hip", "fused.hip", "topk.hip", "driver.hip", "attention.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
@@ -52,7 +52,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
     hipcc = _hipcc()
     headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
-    headers.append(os.path.join(INCLUDE, "streamindex.h"))
+    headers += [os.path.join(INCLUDE, f) for f in os.listdir(INCLUDE) if f.endswith(".h")]
     newest_hdr = max(os.path.getmtime(h) for h in headers)
     objs = []
     for src in SOURCES:

@@ -14,7 +14,8 @@ GiB = 1 << 30
 
 
 def test_library_exports_every_declared_symbol():
-    hdr = open(os.path.join(ROOT, "include", "streamindex.h")).read()
+    hdr = "".join(open(os.path.join(ROOT, "include", f)).read()
+                  for f in sorted(os.listdir(os.path.join(ROOT, "include"))) if f.endswith(".h"))
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     declared = set(re.findall(r"\b(si_[a-z_]+)\s*\(", hdr))
     assert declared == set(binding.EXPORTS), declared ^ set(binding.EXPORTS)
