@@ -82,6 +82,68 @@ def _phase_budget(P, words, steps, kernel_ms_per_step):
     return out
 
 
+def _consumer(P, W, wl, K, out_idx, args, dev):
+    """Times si_sparse_attention on the lists the indexer just wrote (64 attention heads of the
+    cache's head dimension, scale 1/sqrt(D)), checks sampled rows against the oracle."""
+    import numpy as np
+    import torch
+    H_A, D, n_win = 64, wl.D, args.window
+    scale = 1.0 / float(np.sqrt(D))
+    g = torch.Generator(device=dev)
+    g.manual_seed(wl.seed * 1000003 + 5)
+    qa = torch.empty((wl.B, wl.S, H_A, D), dtype=torch.bfloat16, device=dev)
+    for s0 in range(0, wl.S, 8192):  # chunked: keeps the fp32 temporary small
+        s1 = min(wl.S, s0 + 8192)
+        qa[:, s0:s1] = torch.randn((wl.B, s1 - s0, H_A, D), generator=g, device=dev).to(torch.bfloat16)
+    out = torch.empty((wl.B, wl.S, H_A, D), dtype=torch.float32, device=dev)
+    run = lambda: P.si_sparse_attention(qa, K, out_idx, wl.m, wl.mask_mode, n_win, scale, out)  # noqa: E731
+    for _ in range(max(1, args.warmup)):
+        run()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    ev[0].record()
+    for i in range(args.steps):
+        run()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    ms = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps))
+    # |U(t)| = entries outside the window + the window, summed over the queries
+    t = torch.arange(wl.S, device=dev)
+    legal = torch.clamp((t + 1) // wl.m, max=wl.T) if wl.mask_mode else torch.full_like(t, wl.T)
+    w0 = torch.clamp(legal - n_win, min=0)
+    n_u = 0
+    for s0 in range(0, wl.S, 65536):
+        s1 = min(wl.S, s0 + 65536)
+        e = out_idx[:, s0:s1]
+        inside = (e >= w0[None, s0:s1, None]) & (e < legal[None, s0:s1, None])
+        n_u += int(((e >= 0) & ~inside).sum()) + wl.B * int((legal[s0:s1] - w0[s0:s1]).sum())
+    flop = 4.0 * n_u * H_A * D  # two products of 2 * |U| * H_A * D each
+    med = ms[len(ms) // 2]
+    res = {
+        "kernel": "sparse_attention_kernel", "heads": H_A, "D": D, "window": n_win, "scale": scale,
+        "ms_per_step": med, "ms_per_step_min": ms[0], "selected_pairs": n_u,
+        "pairs_per_s": n_u / (med * 1e-3),
+        "roofline": {"bound": "mfma", "achieved": flop / (med * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": flop / (med * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                     "gathered_bytes_per_step": n_u * D * 2, "traffic": None},
+        "bytes_qa_out": int(qa.numel() * 2 + out.numel() * 4),
+    }
+    if args.oracle_rows > 0:
+        from oracle import oracle as O
+        from tests import parity
+        rows = W.sample_rows(wl, min(args.oracle_rows, 512))
+        rows_d = torch.from_numpy(rows).to(dev)
+        ref = O.sparse_attention_rows(
+            W.bf16_bits(qa[0].index_select(0, rows_d)), W.bf16_bits(K),
+            out_idx[0].index_select(0, rows_d).cpu().numpy(), np.zeros(len(rows), dtype=np.int32), rows,
+            wl.m, wl.mask_mode, n_win, scale, n_threads=parity.host_threads())
+        got = out[0].index_select(0, rows_d).cpu().numpy()
+        err = np.abs(got - ref) / (np.abs(ref) + 1.0)
+        assert float(err.max()) <= parity.REL, float(err.max())
+        res["parity_on_sample"] = {"rows": int(len(rows)), "max_scaled_err": float(err.max())}
+    return res
+
+
 def _pair_overlap(log_words, n_events, rate_khz):
     """From the phase-change logs of two workgroups (in the narrow shape: the two that share compute
     unit 0's slot): over the time both were running, the share of time in which 0, 1 or 2 of them
@@ -140,6 +202,10 @@ def main() -> int:
     ap.add_argument("--phases", action="store_true",
                     help="single-pass schedule, V4 head shape, k <= 1024: run the instrumented kernel "
                          "and add its per-phase time budget to the JSON line")
+    ap.add_argument("--consumer", action="store_true",
+                    help="also time si_sparse_attention (attention over TopK(t) U Window(t)) on the index "
+                         "lists this run produced, and add a \"consumer\" object to the JSON line")
+    ap.add_argument("--window", type=int, default=128, help="--consumer: keys of Window(t)")
     ap.add_argument("--calibration-mib", type=int, default=0,
                     help="also run one plain elementwise kernel reading and writing this many MiB "
                          "(a known-size reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -326,6 +392,8 @@ def main() -> int:
 
     if phase_budget is not None:
         result["phase_budget"] = phase_budget
+    if args.consumer:
+        result["consumer"] = _consumer(P, W, wl, K, out_idx, args, dev)
 
     if args.oracle_rows > 0:
         from oracle import oracle as O  # cpu_baseline leg only
