@@ -16,7 +16,7 @@
  *   tiled       one launch per (c_S x c_T) tile; the largest transient is one candidate list of
  *               at most c_T (score, index) pairs per query of the current query tile, inside
  *               `workspace` (O(B * c_S * c_T) bytes) -- the design-space axes of Section 6.5;
- *   single pass one persistent kernel; 8 queries per workgroup walk their whole key range and
+ *   single pass one persistent kernel; 8 (or 4) queries per workgroup walk their whole key range and
  *               the only transient is a short row buffer per resident wave (tens of MB).
  * The result does not depend on the schedule or on (c_S, c_T): it is bit-identical.
  *
@@ -112,7 +112,7 @@ si_status si_indexer_topk_tiled(const void* q, const void* K, const float* w,
                                 int32_t* out_idx, float* out_score, void* workspace,
                                 size_t workspace_bytes, void* stream);
 
-/* The same result by the single-pass schedule: every group of 8 consecutive queries is taken
+/* The same result by the single-pass schedule: every group of 8 (or 4) consecutive queries is taken
  * through its whole legal key range by one resident workgroup, which filters, merges (a row is
  * cut back to its best k whenever it has collected 2k candidates) and writes out without
  * leaving the kernel.  No (c_S x c_T) candidate lists exist: the workspace holds one short row

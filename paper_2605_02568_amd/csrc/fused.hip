@@ -31,7 +31,7 @@ static_assert(kFusedRowSlack >= kSweepOvershoot, "a stopped sweep must not run p
 constexpr int kWarmupMaxKeys = 8192;
 
 // The kernel is compiled for two ranges of k (KMAX = 1024 and kFusedMaxK = 2048): a whole row
-// must fit the registers of a wave, and the sort area of the 8 waves must fit the LDS.
+// must fit the registers of a wave, and the sort area of the workgroup's waves must fit the LDS.
 template <int KMAX>
 constexpr int fused_reg_keys() { return (kFusedTriggerMul * KMAX + 384 + 63) / 64; }
 template <int D, int KMAX, int WAVES>

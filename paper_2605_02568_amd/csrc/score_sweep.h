@@ -1,7 +1,7 @@
 // The key sweep of the fused score kernel (Section 5, "fused score kernel"; Section 1 for the
 // formula):
 //   score[t, s] = sum_h w[t,h] * max(0, sum_d q[t,h,d] * K[s,d])
-// for the 8 queries of one workgroup against a run of consecutive keys.  bf16 operands, fp32
+// for the queries of one workgroup (one per wave) against a run of consecutive keys.  bf16 operands, fp32
 // MFMA accumulation, ReLU and the weighted head sum done on the MFMA result registers; the
 // per-head values never leave the wave.
 //
@@ -11,9 +11,10 @@
 //     8 bf16.  Keys are the N side, 32 per MFMA, read from LDS.
 //   - the 32x32 result puts one key per lane column (lane & 31) and 16 heads per lane, so the
 //     head sum is 16 in-lane FMAs per head block plus one exchange between lane and lane^32.
-//   - a workgroup is 8 waves = 8 consecutive queries sharing each staged block of 128 keys.
-//     Key blocks travel HBM/L2 -> LDS directly (global_load_lds, no register round trip) into
-//     a ring of three buffers, two blocks ahead of the one being multiplied.
+//   - a workgroup is 8 (or 4, see SweepShape) waves = consecutive queries sharing each staged
+//     block of 128 (64) keys.  Key blocks travel HBM/L2 -> LDS directly (buffer_load ... lds, no
+//     register round trip) into a ring of three (four) buffers, two (three) blocks ahead of the
+//     one being multiplied.
 //   - the loop is a software pipeline over 32-key sub-blocks: MFMAs of sub-block g, epilogue
 //     of sub-block g-1 and LDS reads for sub-block g+1 are interleaved instruction by
 //     instruction, so the matrix pipe, the vector ALU and the LDS work at the same time.
@@ -199,17 +200,17 @@ struct SweepOut {
 };
 
 // Sweeps keys [0, n_keys) of Kb (a multiple of 128 is covered: key rows from `key_clamp` on read
-// as zero and are never emitted; key_clamp * 2D < 2^32).  All 8 waves of the workgroup must call it together
+// as zero and are never emitted; key_clamp * 2D < 2^32).  All WAVES waves of the workgroup must call it together
 // with the same Kb, key_clamp and n_keys > 0.
 //
 // STOPPABLE (filter mode): the sweep also ends, for the whole workgroup at the same key, once
 // some wave holds at least `trigger` keys.  Such a wave sets flags[step parity] (LDS, 2 ints,
-// zero on entry) after its 128-key step, and everybody reads the word of the previous step behind
-// the step's barrier, so the decision is uniform without another barrier and nothing has to be
-// cleared on the way.  A row can therefore grow to at most trigger + 319 keys before the sweep
-// returns.
+// zero on entry) after its step (one key chunk), and everybody reads the word of the previous step
+// behind the step's barrier, so the decision is uniform without another barrier and nothing has to
+// be cleared on the way.  A row can therefore grow to at most trigger + kSweepOvershoot (319) keys
+// before the sweep returns (128-key chunks; 191 with 64-key chunks).
 //
-// Returns the number of keys swept (a multiple of 128, or >= n_keys at the natural end).  On
+// Returns the number of keys swept (a multiple of the chunk, or >= n_keys at the natural end).  On
 // return every global -> LDS transfer the workgroup issued has landed for the calling wave;
 // a workgroup barrier must follow before the LDS is reused.
 template <int D, int HB, bool FILTER, bool STOPPABLE, bool PREFETCHED = false, int WAVES = kWaves>

@@ -56,7 +56,7 @@ __device__ inline void poison_row(int32_t* out_idx, float* out_score, int64_t ou
 
 constexpr int kMaxK = 4096;
 constexpr int kMaxHeads = 64;
-constexpr int kQueriesPerBlock = 8;  // score kernel: one query per wave, 8 waves
+constexpr int kQueriesPerBlock = 8;  // score kernel: one query per wave, 8 waves (wide workgroup shape)
 
 // Single-pass schedule (fused.hip): k up to kFusedMaxK (a row must fit a wave's registers); a row is merged once it holds
 // kFusedTriggerMul * k keys; at most kFusedSlots workgroups are resident (one per compute unit

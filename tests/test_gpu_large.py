@@ -156,6 +156,8 @@ def test_flash_1m_within_8gb_workspace(oracle):
     _say(f"flash_1m single pass, workspace={fused_bytes}")
     assert 0 < fused_bytes < 64 * 2**20
     assert _same_bits(out, _run_default(wl, q, K, w, fused_bytes))
+    _say("flash_1m single pass, narrow workgroups")
+    assert _same_bits(out, _run_shape(wl, q, K, w, 4))
 
 
 # ------------------------------------------------------------------ the paper's other sweeps at full size
