@@ -191,3 +191,28 @@ def test_flash_256k_query_tile_sweep_is_bit_identical(oracle):
     for c_S in (1024, 4096, 16384):
         _say(f"{wl.name} c_S={c_S} c_T=8192")
         assert _same_bits(ref, _run(wl, q, K, w, c_S, 8192)), c_S
+
+
+def test_flash_64k_consumer_sampled_rows(oracle):
+    """The consumer at an evaluation size (V4-Flash, S = 65,536): attention over the indexer's own
+    lists plus a window of 128 keys, 64 heads; sampled and edge rows against the oracle."""
+    wl = W.CONFIGS["flash_64k"]
+    q, K, w, _ = W.make_inputs(wl, device=DEV)
+    idx, _ = _run_default(wl, q, K, w, P.si_fused_workspace_bytes(wl.B, wl.S, wl.H, wl.D, wl.T, wl.k))
+    g = torch.Generator(device=DEV)
+    g.manual_seed(77)
+    H_A, n_win, scale = 64, 128, 1.0 / float(np.sqrt(wl.D))
+    qa = torch.randn((wl.B, wl.S, H_A, wl.D), generator=g, device=DEV).to(torch.bfloat16)
+    out = torch.full((wl.B, wl.S, H_A, wl.D), float("nan"), dtype=torch.float32, device=DEV)
+    P.si_sparse_attention(qa, K, idx, wl.m, wl.mask_mode, n_win, scale, out)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())
+    assert bool((out[0, :wl.m - 1] == 0).all())  # rows without a legal key
+    rows = W.sample_rows(wl, 192)
+    rows_d = torch.from_numpy(rows).to(DEV)
+    ref = oracle.sparse_attention_rows(
+        W.bf16_bits(qa[0].index_select(0, rows_d)), W.bf16_bits(K), idx[0].index_select(0, rows_d).cpu().numpy(),
+        np.zeros(len(rows), dtype=np.int32), rows, wl.m, wl.mask_mode, n_win, scale, n_threads=parity.host_threads())
+    err = np.abs(out[0].index_select(0, rows_d).cpu().numpy() - ref) / (np.abs(ref) + 1.0)
+    _say(f"flash_64k consumer: {len(rows)} rows, max scaled error {float(err.max()):.2e}")
+    assert float(err.max()) <= parity.REL
