@@ -82,6 +82,34 @@ def _phase_budget(P, words, steps, kernel_ms_per_step):
     return out
 
 
+def _library_gemm_context(torch, wl, dev):
+    """What this box's library bf16 GEMM (torch.matmul -> hipBLASLt) sustains, as context for the
+    fraction of the published peak: a large square product (the practical MFMA ceiling of the
+    box at its power limit), and the indexer's own contraction shape with the scores written to
+    HBM in bf16 (one 64-query x 8192-key slab of the materializing formulation, before any
+    ReLU, head sum or top-k)."""
+    out = {}
+    for name, (M, N, Kd) in {"square_8192": (8192, 8192, 8192), "deep_8192x8192x65536": (8192, 8192, 65536),
+                             "score_shape_materialized": (1024 * wl.H, 8192, wl.D)}.items():
+        a = torch.randn((M, Kd), device=dev).to(torch.bfloat16)
+        b = torch.randn((N, Kd), device=dev).to(torch.bfloat16)
+        c = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+        for _ in range(3):
+            torch.matmul(a, b.t(), out=c)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        iters = 10
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(iters):
+            torch.matmul(a, b.t(), out=c)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / iters
+        out[name] = {"M": M, "N": N, "K": Kd, "ms": ms, "tflops": 2.0 * M * N * Kd / ms / 1e9}
+        del a, b, c
+    return out
+
+
 def _consumer(P, W, wl, K, out_idx, args, dev):
     """Times si_sparse_attention on the lists the indexer just wrote (64 attention heads of the
     cache's head dimension, scale 1/sqrt(D)), checks sampled rows against the oracle."""
@@ -206,6 +234,9 @@ def main() -> int:
                     help="also time si_sparse_attention (attention over TopK(t) U Window(t)) on the index "
                          "lists this run produced, and add a \"consumer\" object to the JSON line")
     ap.add_argument("--window", type=int, default=128, help="--consumer: keys of Window(t)")
+    ap.add_argument("--gemm-context", action="store_true",
+                    help="also time the library's bf16 GEMM on this box (a square product and the "
+                         "indexer's contraction shape written out) and add the rates to the JSON line")
     ap.add_argument("--calibration-mib", type=int, default=0,
                     help="also run one plain elementwise kernel reading and writing this many MiB "
                          "(a known-size reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -392,6 +423,8 @@ def main() -> int:
 
     if phase_budget is not None:
         result["phase_budget"] = phase_budget
+    if args.gemm_context:
+        result["library_gemm_context"] = _library_gemm_context(torch, wl, dev)
     if args.consumer:
         result["consumer"] = _consumer(P, W, wl, K, out_idx, args, dev)
 
