@@ -58,10 +58,22 @@ __device__ __forceinline__ int tile_slot(int row, int piece) {
     return row * kPieces + (piece ^ ((row / kRowsPer256) % kPieces));
 }
 
+// The value lane (l ^ 32) holds, by v_permlane32_swap instead of an LDS round trip: of the swap's two
+// results one carries the low half-wave's values in both halves, the other the high half-wave's;
+// each lane picks the one that is not its own.
+__device__ __forceinline__ float other_half(float v) {
+    const unsigned bits = __builtin_bit_cast(unsigned, v);
+    const auto both = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);
+    return __builtin_bit_cast(float, (threadIdx.x & 32) ? both[0] : both[1]);
+}
+
 // One workgroup per query; HW waves of 64 lanes, wave w owns heads [32 w, 32 w + 32).
 // Dynamic LDS: 2 tiles of 32 x D bf16, then the query's key list (k + n_win ints, padded to a tile).
+// Two waves per SIMD are asked for explicitly: with a register budget of 256 the compiler keeps the
+// accumulators in ordinary VGPRs; left to a budget of 512 it parks them in AGPRs and copies all 64
+// of them out and back around the rescale test of every tile.
 template <int D, int HW>
-__global__ __launch_bounds__(64 * HW)
+__global__ __launch_bounds__(64 * HW) __attribute__((amdgpu_waves_per_eu(2)))
 void sparse_attention_kernel(const __bf16* __restrict__ qa, const __bf16* __restrict__ Kc,
                              const int32_t* __restrict__ idx, int S, int H, int T, int m, int mask_mode,
                              int k, int n_win, float scale_log2e, float* __restrict__ out) {
@@ -121,16 +133,21 @@ void sparse_attention_kernel(const __bf16* __restrict__ qa, const __bf16* __rest
     typedef __attribute__((address_space(3))) void lds_void;
     typedef __attribute__((address_space(1))) const void gbl_void;
     auto gather = [&](int tile, int buf) {
+        int key[kLoadsPerWave];  // all of this lane's list entries first: one LDS round trip, not one per load
+#pragma unroll
+        for (int i = 0; i < kLoadsPerWave; ++i) {
+            const int unit = (wave * kLoadsPerWave + i) * 64 + lane;  // 16-byte LDS slot this lane fills
+            key[i] = s_list[tile * kTileKeys + unit / kPieces];
+        }
 #pragma unroll
         for (int i = 0; i < kLoadsPerWave; ++i) {
             const int blk = wave * kLoadsPerWave + i;         // 1 KiB block of the tile
-            const int unit = blk * 64 + lane;                  // 16-byte LDS slot this lane fills
+            const int unit = blk * 64 + lane;
             const int r = unit / kPieces;                      // tile row
             const int slot = unit % kPieces;
             constexpr int kRowsPer256 = 256 / kRowBytes;
             const int piece = slot ^ ((r / kRowsPer256) % kPieces);
-            const int key = s_list[tile * kTileKeys + r];
-            const char* src = reinterpret_cast<const char*>(Kb) + static_cast<int64_t>(key) * kRowBytes + piece * 16;
+            const char* src = reinterpret_cast<const char*>(Kb) + static_cast<int64_t>(key[i]) * kRowBytes + piece * 16;
             __builtin_amdgcn_global_load_lds((gbl_void*)src, (lds_void*)(lds + buf * kTileBytes + blk * 1024), 16, 0, 0);
         }
     };
@@ -192,16 +209,18 @@ void sparse_attention_kernel(const __bf16* __restrict__ qa, const __bf16* __rest
         float x[16];
 #pragma unroll
         for (int j = 0; j < 16; ++j) x[j] = sacc[j] * scale_log2e;
-        if (tile == n_tiles - 1) {  // rows past the end of U(t) take no weight
+        if (tile == n_tiles - 1 && n_u < n_tiles * kTileKeys) {  // rows past the end of U(t) take no weight
+            float dead = -__builtin_huge_valf();
+            asm volatile("" : "+v"(dead));  // keeps this rare block a branch instead of 16 selects per tile
             const int live = n_u - tile * kTileKeys;
 #pragma unroll
             for (int j = 0; j < 16; ++j)
-                if (8 * (j >> 2) + 4 * half + (j & 3) >= live) x[j] = -__builtin_huge_valf();
+                if (8 * (j >> 2) + 4 * half + (j & 3) >= live) x[j] = dead;
         }
         float tmax = x[0];
 #pragma unroll
         for (int j = 1; j < 16; ++j) tmax = fmaxf(tmax, x[j]);
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));  // the tile's maximum for this head (finite)
+        tmax = fmaxf(tmax, other_half(tmax));  // the tile's maximum for this head (finite)
         const bool raise = tmax > m_ref + kRescaleSlack;
         if (__ballot(raise) != 0ull) {  // rare after the first tiles
             const float m_new = raise ? tmax : m_ref;
@@ -241,7 +260,7 @@ void sparse_attention_kernel(const __bf16* __restrict__ qa, const __bf16* __rest
     }
 
     // ---- out[t, head, d] = O^T[d, head] / l : register j of block db = d row 32 db + 8 (j / 4) + 4 half + j % 4
-    const float l_all = l_sum + __shfl_xor(l_sum, 32);
+    const float l_all = l_sum + other_half(l_sum);
     const float inv = 1.0f / l_all;
     const int h = 32 * wave + col;
     if (h < H) {
