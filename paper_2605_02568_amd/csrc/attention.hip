@@ -31,6 +31,7 @@
 
 #include <algorithm>
 #include <atomic>
+#include <type_traits>
 
 #include "si_internal.h"
 #include "streamindex_attention.h"
@@ -162,6 +163,15 @@ void sparse_attention_kernel(const __bf16* __restrict__ qa, const __bf16* __rest
         for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(src + ks * 16);
     }
 
+    // A negative scale goes into the query operand: flipping the sign bit of a bf16 is exact, every
+    // product and partial sum changes sign and nothing else, so the scores are those of (-q, -scale).
+    if (scale_log2e < 0.0f) {
+        typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            qf[ks] = __builtin_bit_cast(bf16x8, __builtin_bit_cast(uintx4, qf[ks]) ^ 0x80008000u);
+        scale_log2e = -scale_log2e;
+    }
     // LDS byte offsets that do not depend on the tile: first product, row = col, piece 2 ks + half
     int ka[KS];
 #pragma unroll
@@ -190,8 +200,10 @@ void sparse_attention_kernel(const __bf16* __restrict__ qa, const __bf16* __rest
     float m_ref = -__builtin_huge_valf();  // reference maximum of this lane's head (log2 domain)
     float l_sum = 0.0f;                    // sum of p over this half-wave's keys
 
-    for (int tile = 0; tile < n_tiles; ++tile) {
-        const int buf = tile & 1;
+    // One tile; the buffer index is a compile-time constant so that every LDS address of the tile is
+    // a loop-invariant register plus an immediate offset.
+    auto step = [&](int tile, auto buf_tag) {
+        constexpr int buf = decltype(buf_tag)::value;
         // tile `tile` has landed for every wave; everyone is done with tile - 1, whose buffer the next
         // gather overwrites
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
@@ -206,21 +218,22 @@ void sparse_attention_kernel(const __bf16* __restrict__ qa, const __bf16* __rest
             const bf16x8 kf = *reinterpret_cast<const bf16x8*>(tb + ka[ks]);
             sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc, 0, 0, 0);
         }
-        float x[16];
-#pragma unroll
-        for (int j = 0; j < 16; ++j) x[j] = sacc[j] * scale_log2e;
-        if (tile == n_tiles - 1 && n_u < n_tiles * kTileKeys) {  // rows past the end of U(t) take no weight
-            float dead = -__builtin_huge_valf();
-            asm volatile("" : "+v"(dead));  // keeps this rare block a branch instead of 16 selects per tile
+        // The scale is >= 0 here (a negative one was moved into the query operand), so the largest scaled
+        // score is the largest raw one times the scale, and scale and reference go into one fma per key.
+        const bool ragged = tile == n_tiles - 1 && n_u < n_tiles * kTileKeys;  // rows past the end of U(t): rare
+        if (ragged) {
+            float low = -3.0e38f;
+            asm volatile("" : "+v"(low));  // keeps this block a branch instead of 16 selects per tile
             const int live = n_u - tile * kTileKeys;
 #pragma unroll
             for (int j = 0; j < 16; ++j)
-                if (8 * (j >> 2) + 4 * half + (j & 3) >= live) x[j] = dead;
+                if (8 * (j >> 2) + 4 * half + (j & 3) >= live) sacc[j] = low;  // out of the maximum; weight zeroed below
         }
-        float tmax = x[0];
+        float smax = sacc[0];
 #pragma unroll
-        for (int j = 1; j < 16; ++j) tmax = fmaxf(tmax, x[j]);
-        tmax = fmaxf(tmax, other_half(tmax));  // the tile's maximum for this head (finite)
+        for (int j = 1; j < 16; ++j) smax = fmaxf(smax, sacc[j]);
+        float tmax = smax * scale_log2e;
+        tmax = fmaxf(tmax, other_half(tmax));  // the tile's maximum for this head (finite: row 0 of a tile is live)
         const bool raise = tmax > m_ref + kRescaleSlack;
         if (__ballot(raise) != 0ull) {  // rare after the first tiles
             const float m_new = raise ? tmax : m_ref;
@@ -232,15 +245,37 @@ void sparse_attention_kernel(const __bf16* __restrict__ qa, const __bf16* __rest
             l_sum *= alpha;
             m_ref = m_new;
         }
-        // weights, their two bf16 parts
+        float p[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) p[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[j], scale_log2e, -m_ref));
+        if (ragged) {
+            float none = 0.0f;
+            asm volatile("" : "+v"(none));
+            const int live = n_u - tile * kTileKeys;
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                if (8 * (j >> 2) + 4 * half + (j & 3) >= live) p[j] = none;
+        }
+        // weights as two bf16 parts, two keys per conversion: hi = bf16(p), lo = bf16(p - hi)
+        typedef float floatx2 __attribute__((ext_vector_type(2)));
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+        uintx4 hi_bits[2], lo_bits[2];
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) {
+            const float p0 = p[2 * jj], p1 = p[2 * jj + 1];
+            l_sum += p0 + p1;
+            const unsigned hb = __builtin_bit_cast(unsigned, __builtin_convertvector(floatx2{p0, p1}, bf16x2));
+            const float r0 = p0 - __builtin_bit_cast(float, hb << 16);
+            const float r1 = p1 - __builtin_bit_cast(float, hb & 0xFFFF0000u);
+            hi_bits[jj >> 2][jj & 3] = hb;
+            lo_bits[jj >> 2][jj & 3] = __builtin_bit_cast(unsigned, __builtin_convertvector(floatx2{r0, r1}, bf16x2));
+        }
         bf16x8 p_hi[2], p_lo[2];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const float p = __builtin_amdgcn_exp2f(x[j] - m_ref);
-            l_sum += p;
-            const __bf16 hi = static_cast<__bf16>(p);
-            p_hi[j >> 3][j & 7] = hi;
-            p_lo[j >> 3][j & 7] = static_cast<__bf16>(p - static_cast<float>(hi));
+        for (int u = 0; u < 2; ++u) {
+            p_hi[u] = __builtin_bit_cast(bf16x8, hi_bits[u]);
+            p_lo[u] = __builtin_bit_cast(bf16x8, lo_bits[u]);
         }
         // O^T += Vtile^T . P^T : contraction index e of step u <-> tile row 16 u + 8 (e / 4) + 4 half + e % 4
         // on both operands
@@ -257,6 +292,10 @@ void sparse_attention_kernel(const __bf16* __restrict__ qa, const __bf16* __rest
                 acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p_hi[u], acc[db], 0, 0, 0);
                 acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p_lo[u], acc[db], 0, 0, 0);
             }
+    };
+    for (int tile = 0; tile < n_tiles; tile += 2) {
+        step(tile, std::integral_constant<int, 0>{});
+        if (tile + 1 < n_tiles) step(tile + 1, std::integral_constant<int, 1>{});
     }
 
     // ---- out[t, head, d] = O^T[d, head] / l : register j of block db = d row 32 db + 8 (j / 4) + 4 half + j % 4

@@ -110,6 +110,12 @@ def test_degenerate_rows_and_scales(oracle):
     _check(oracle, qa, K, idx, m, 1, 3, 30.0)
     _check(oracle, qa, K, idx, m, 1, 3, 1e-6)
     _check(oracle, torch.zeros_like(qa), K, idx, m, 1, 3, 1.0)
+    # negative scale (the kernel moves its sign into the query operand), zero scale (uniform weights
+    # over a ragged last tile: the rows past the end must still weigh nothing), a vanishing one
+    _check(oracle, qa, K, idx, m, 1, 3, -0.3)
+    _check(oracle, qa, K, idx, m, 1, 3, 0.0)
+    _check(oracle, qa, K, idx, m, 1, 3, -0.0)
+    _check(oracle, qa, K, idx, m, 1, 3, 1e-30)
     # logits far apart between tiles: the reference maximum has to be raised late in the list
     T2 = 200
     qa2, K2 = _problem(4, 1, 4, 8, 64, T2)
