@@ -13,6 +13,9 @@ OBJ_DIR = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libstreamindex.so")
 
 SOURCES = ["score_tile.hip", "fused.hip", "topk.hip", "driver.hip", "attention.hip"]
+# a stand-alone measurement program (register-only MFMA/VALU issue probe), not linked into the library
+PROBE_SOURCE = "issue_probe.hip"
+PROBE = os.path.join(PKG, "issue_probe")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
@@ -48,7 +51,8 @@ def source_hash() -> str:
 
 
 def build(force: bool = True, verbose: bool = False) -> str:
-    """Compile every HIP source and link the shared library.  Returns its path."""
+    """Compile every HIP source, link the shared library and the stand-alone probe.  Returns the
+    library's path."""
     os.makedirs(OBJ_DIR, exist_ok=True)
     hipcc = _hipcc()
     headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
@@ -66,6 +70,12 @@ def build(force: bool = True, verbose: bool = False) -> str:
             subprocess.run(cmd, check=True)
     if force or not os.path.exists(LIB) or any(os.path.getmtime(LIB) < os.path.getmtime(o) for o in objs):
         cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+        if verbose:
+            print(" ".join(cmd), file=sys.stderr)
+        subprocess.run(cmd, check=True)
+    probe_src = os.path.join(CSRC, PROBE_SOURCE)
+    if force or not os.path.exists(PROBE) or os.path.getmtime(PROBE) < os.path.getmtime(probe_src):
+        cmd = [hipcc, *[f for f in HIPCC_FLAGS if f != "-fPIC"], probe_src, "-o", PROBE]
         if verbose:
             print(" ".join(cmd), file=sys.stderr)
         subprocess.run(cmd, check=True)
