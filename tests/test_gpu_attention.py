@@ -1,5 +1,7 @@
 """GPU parity of the index lists' consumer (si_sparse_attention: attention over TopK(t) U Window(t),
 Section 3, step 4) against the CPU oracle, element by element, through the C ABI's binding."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -66,6 +68,32 @@ def test_random_lists_all_rows(oracle, B, S, H, D, T, m, k, mask, n_win):
     idx = _random_lists(np.random.default_rng(S), B, S, T, k, m, mask)
     worst = _check(oracle, qa, K, idx, m, mask, n_win, 1.0 / np.sqrt(D))
     print(f"  max scaled error {worst:.2e}", flush=True)
+
+
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        T = int(rng.integers(1, 700))
+        cases.append(dict(
+            B=int(rng.integers(1, 3)), S=int(rng.integers(1, 40)), H=int(rng.choice([1, 7, 32, 33, 64])),
+            D=int(rng.choice([64, 128])), T=T, m=int(rng.choice([1, 2, 4, 16])),
+            k=int(rng.choice([1, 5, 31, 32, 33, 64, 100, 257])), mask=int(rng.integers(0, 2)),
+            n_win=int(rng.choice([0, 1, 31, 32, 33, 64, 200])),
+            scale=float(rng.choice([0.09, -0.2, 1.5, 0.0, 1e-4])), seed=500 + i))
+    return cases
+
+
+# 16 seeded cases by default; SI_FUZZ_CASES=N runs the first N of the same seeded sequence
+@pytest.mark.parametrize("c", _random_cases(int(os.environ.get("SI_FUZZ_CASES", "16")), 20260601),
+                         ids=lambda c: f"S{c['S']}T{c['T']}H{c['H']}D{c['D']}k{c['k']}w{c['n_win']}s{c['seed']}")
+def test_random_shapes_windows_and_scales(oracle, c):
+    """Seeded shapes: set sizes on both sides of the 32-key tile and of the two-tile unrolling of
+    the kernel's loop, every head split, both masks, scales of either sign and zero."""
+    print("attention", c, flush=True)
+    qa, K = _problem(c["seed"], c["B"], c["S"], c["H"], c["D"], c["T"])
+    idx = _random_lists(np.random.default_rng(c["seed"]), c["B"], c["S"], c["T"], c["k"], c["m"], c["mask"])
+    _check(oracle, qa, K, idx, c["m"], c["mask"], c["n_win"], c["scale"])
 
 
 def test_lists_from_the_indexer(oracle):
