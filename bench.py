@@ -146,6 +146,19 @@ def _consumer(P, W, wl, K, out_idx, args, dev):
         inside = (e >= w0[None, s0:s1, None]) & (e < legal[None, s0:s1, None])
         n_u += int(((e >= 0) & ~inside).sum()) + wl.B * int((legal[s0:s1] - w0[s0:s1]).sum())
     flop = 4.0 * n_u * H_A * D  # two products of 2 * |U| * H_A * D each
+    # measured traffic from the committed rocprofv3 summary, only if it was taken on this attention.hip
+    import hashlib
+    sha = hashlib.sha256(open(os.path.join(ROOT, "paper_2605_02568_amd", "csrc", "attention.hip"), "rb").read()).hexdigest()[:16]
+    traffic, traffic_sha = None, None
+    summary = os.path.join(ROOT, "profiles", f"sparse_attention_{wl.name}.txt")
+    if n_win == 128 and os.path.exists(summary):
+        for line in open(summary):
+            if line.startswith("traffic_bytes_per_launch"):
+                traffic = float(line.split()[1])
+            if line.startswith("attention_source_sha16"):
+                traffic_sha = line.split()[1]
+        if traffic_sha != sha:
+            traffic = None
     med = ms[len(ms) // 2]
     res = {
         "kernel": "sparse_attention_kernel", "heads": H_A, "D": D, "window": n_win, "scale": scale,
@@ -153,7 +166,9 @@ def _consumer(P, W, wl, K, out_idx, args, dev):
         "pairs_per_s": n_u / (med * 1e-3),
         "roofline": {"bound": "mfma", "achieved": flop / (med * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": flop / (med * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-                     "gathered_bytes_per_step": n_u * D * 2, "traffic": None},
+                     "gathered_bytes_per_step": n_u * D * 2, "traffic": traffic,
+                     "traffic_measured_on_source": traffic_sha},
+        "attention_source_sha16": sha,
         "bytes_qa_out": int(qa.numel() * 2 + out.numel() * 4),
     }
     if args.oracle_rows > 0:
